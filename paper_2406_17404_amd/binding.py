@@ -1,0 +1,239 @@
+"""ctypes binding of libtrjacobi.so: the same names and arguments as include/trjacobi.h.
+
+Only argument marshalling happens here: torch tensors stand for device buffers (their
+``data_ptr()`` is passed), the current torch stream is passed as the HIP stream, and a
+non-zero status raises :class:`TrjError`.  Nothing is computed in Python and nothing
+falls back to the CPU: if the shared library is not built, importing symbols from it
+raises immediately.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtrjacobi.so")
+
+N_MAX = 128
+KV_BLOCK = 32
+F32, BF16 = 0, 1
+PACK_PLAIN, PACK_QKV, PACK_GATE_UP = 0, 1, 2
+STATUS = {0: "TRJ_OK", -1: "TRJ_ERR_NULLPTR", -2: "TRJ_ERR_BAD_SHAPE", -3: "TRJ_ERR_BAD_DTYPE",
+          -4: "TRJ_ERR_TREE_TOO_LARGE", -5: "TRJ_ERR_WORKSPACE_TOO_SMALL", -6: "TRJ_ERR_HIP"}
+
+
+class TrjError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} returned {STATUS.get(status, status)}")
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [("g_attn", C.c_void_p), ("wqkv", C.c_void_p), ("wo", C.c_void_p),
+                ("g_ffn", C.c_void_p), ("w_gate_up", C.c_void_p), ("w_down", C.c_void_p)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("g_final", C.c_void_p), ("w_lm", C.c_void_p),
+                ("h_layers", C.POINTER(LayerWeights))]
+
+
+_lib = None
+_vp, _i32, _sz, _f = C.c_void_p, C.c_int32, C.c_size_t, C.c_float
+_SIGS = {
+    "trj_version": (C.c_char_p, []),
+    "trj_last_hip_error": (_i32, []),
+    "trj_set_tunable": (_i32, [C.c_char_p, _i32]),
+    "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
+    "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "trj_kv_pack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "trj_kv_unpack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "trj_linear": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp, _vp]),
+    "trj_tree_mask": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "tree_attention": (_i32, [_vp] * 7 + [_i32] * 7 + [_f, _vp, _sz, _vp, _vp]),
+    "accept_path": (_i32, [_vp] * 4 + [_i32] * 3 + [_vp] * 7),
+    "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
+    "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
+                       [_vp] * 5 + [_i32] * 3 + [_vp, _sz] + [_vp] * 9),
+}
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2406_17404_amd.build` (there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def exported_symbols() -> List[str]:
+    return list(_SIGS)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise TrjError(fn, status)
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise ValueError(f"unsupported dtype {t}")
+
+
+def trj_version() -> str:
+    return lib().trj_version().decode()
+
+
+def trj_set_tunable(name: str, value: int) -> None:
+    _check("trj_set_tunable", lib().trj_set_tunable(name.encode(), int(value)))
+
+
+def trj_workspace_bytes(desc: ModelDesc, t_max: int, b_max: int, l_max: int) -> int:
+    n = _sz(0)
+    _check("trj_workspace_bytes", lib().trj_workspace_bytes(C.byref(desc), t_max, b_max, l_max, C.byref(n)))
+    return int(n.value)
+
+
+def trj_pack_weight(dst, src, n_out, n_in, dtype, kind, n_heads=0, head_dim=0):
+    _check("trj_pack_weight", lib().trj_pack_weight(_ptr(dst), _ptr(src), n_out, n_in, dtype, kind,
+                                                    n_heads, head_dim, _stream()))
+
+
+def trj_kv_pack(k_pool, v_pool, k_plain, v_plain, n_heads, head_dim, s_pool, slot0, n_slots, dtype):
+    _check("trj_kv_pack", lib().trj_kv_pack(_ptr(k_pool), _ptr(v_pool), _ptr(k_plain), _ptr(v_plain),
+                                            n_heads, head_dim, s_pool, slot0, n_slots, dtype, _stream()))
+
+
+def trj_kv_unpack(k_plain, v_plain, k_pool, v_pool, n_heads, head_dim, s_pool, slot0, n_slots, dtype):
+    _check("trj_kv_unpack", lib().trj_kv_unpack(_ptr(k_plain), _ptr(v_plain), _ptr(k_pool), _ptr(v_pool),
+                                                n_heads, head_dim, s_pool, slot0, n_slots, dtype, _stream()))
+
+
+def trj_linear(x, w_packed, T, n_in, n_out, dtype, split_k, workspace, y):
+    _check("trj_linear", lib().trj_linear(_ptr(x), _ptr(w_packed), T, n_in, n_out, dtype, split_k,
+                                          _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                          _ptr(y), _stream()))
+
+
+def trj_tree_mask(parent, node_off, B, T, depth, anc, status_dev):
+    _check("trj_tree_mask", lib().trj_tree_mask(_ptr(parent), _ptr(node_off), B, T, _ptr(depth),
+                                                _ptr(anc), _ptr(status_dev), _stream()))
+
+
+def tree_attention(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T, n_heads,
+                   head_dim, s_pool, max_seq_slots, dtype, scale, workspace, out):
+    _check("tree_attention", lib().tree_attention(
+        _ptr(q), _ptr(k_layer), _ptr(v_layer), _ptr(parent), _ptr(node_off), _ptr(kv_off),
+        _ptr(prefix_len), B, T, n_heads, head_dim, s_pool, max_seq_slots, dtype, scale,
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), _stream()))
+
+
+def accept_path(logits, tok, parent, node_off, B, T, V, argmax_out, accept_len, best_node, path,
+                bonus_tok, status_dev):
+    _check("accept_path", lib().accept_path(
+        _ptr(logits), _ptr(tok), _ptr(parent), _ptr(node_off), B, T, V, _ptr(argmax_out),
+        _ptr(accept_len), _ptr(best_node), _ptr(path), _ptr(bonus_tok), _ptr(status_dev), _stream()))
+
+
+def kv_compact(k_pool, v_pool, kv_layer_stride, path, accept_len, kv_off, prefix_len, B, n_layers,
+               n_heads, head_dim, s_pool, dtype, new_len):
+    _check("kv_compact", lib().kv_compact(
+        _ptr(k_pool), _ptr(v_pool), kv_layer_stride, _ptr(path), _ptr(accept_len), _ptr(kv_off),
+        _ptr(prefix_len), B, n_layers, n_heads, head_dim, s_pool, dtype, _ptr(new_len), _stream()))
+
+
+def tr_verify_step(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_layer_stride, s_pool, tok,
+                   parent, node_off, kv_off, prefix_len, B, T, max_seq_slots, workspace, logits,
+                   argmax_out, accept_len, best_node, path, bonus_tok, new_len, status_dev):
+    _check("tr_verify_step", lib().tr_verify_step(
+        C.byref(desc), C.byref(weights), _ptr(k_pool), _ptr(v_pool), kv_layer_stride, s_pool,
+        _ptr(tok), _ptr(parent), _ptr(node_off), _ptr(kv_off), _ptr(prefix_len), B, T,
+        max_seq_slots, _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _ptr(logits), _ptr(argmax_out), _ptr(accept_len), _ptr(best_node), _ptr(path),
+        _ptr(bonus_tok), _ptr(new_len), _ptr(status_dev), _stream()))
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def make_desc(shape) -> ModelDesc:
+    """ModelDesc from any object with the ModelShape fields (dtype "f32" / "bf16")."""
+    return ModelDesc(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
+                     shape.vocab, shape.rms_eps, shape.rope_theta, BF16 if shape.dtype == "bf16" else F32)
+
+
+class DeviceWeights:
+    """Owns the packed device copies of a model's weights and the trj_weights struct that
+    points at them.  `add_layer` / `set_globals` take row-major device tensors in the
+    model dtype (norm gains fp32) and pack them with trj_pack_weight."""
+
+    def __init__(self, desc: ModelDesc):
+        self.desc = desc
+        self._keep: List[torch.Tensor] = []
+        self._layers: List[LayerWeights] = []
+        self.struct: Optional[Weights] = None
+        self._embed = self._g_final = self._w_lm = None
+
+    def _pack(self, w: torch.Tensor, kind: int) -> torch.Tensor:
+        n_out, n_in = w.shape
+        dst = torch.empty_like(w)
+        trj_pack_weight(dst, w.contiguous(), n_out, n_in, self.desc.dtype, kind,
+                        self.desc.n_heads, self.desc.head_dim)
+        self._keep.append(dst)
+        return dst
+
+    def _gain(self, g: torch.Tensor) -> torch.Tensor:
+        g = g.to(torch.float32).contiguous()
+        self._keep.append(g)
+        return g
+
+    def add_layer(self, g_attn, wqkv, wo, g_ffn, w_gate_up, w_down) -> None:
+        self._layers.append(LayerWeights(
+            self._gain(g_attn).data_ptr(), self._pack(wqkv, PACK_QKV).data_ptr(),
+            self._pack(wo, PACK_PLAIN).data_ptr(), self._gain(g_ffn).data_ptr(),
+            self._pack(w_gate_up, PACK_GATE_UP).data_ptr(), self._pack(w_down, PACK_PLAIN).data_ptr()))
+
+    def set_globals(self, embed, g_final, w_lm) -> None:
+        self._embed = embed.contiguous()
+        self._keep.append(self._embed)
+        self._g_final = self._gain(g_final)
+        self._w_lm = self._pack(w_lm, PACK_PLAIN)
+
+    def finish(self) -> Weights:
+        assert len(self._layers) == self.desc.n_layers and self._embed is not None
+        arr = (LayerWeights * len(self._layers))(*self._layers)
+        self._arr = arr
+        self.struct = Weights(self._embed.data_ptr(), self._g_final.data_ptr(),
+                              self._w_lm.data_ptr(), C.cast(arr, C.POINTER(LayerWeights)))
+        return self.struct

@@ -1,0 +1,369 @@
+// C-ABI entry points of libtrjacobi: argument checks, workspace carving and the order
+// in which the kernels of the verify step are enqueued.  No arithmetic lives here.
+#include <atomic>
+#include <cstring>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace trj {
+
+Tunables g_tune;
+static std::atomic<int> g_last_hip_error{0};
+void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+
+// bump allocator over the caller's workspace; with base == nullptr it only measures
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t count) {
+    off = align_up(off, 256);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct TreeWs {
+  int32_t *depth, *row_slot, *row_pos, *row_seq, *status;
+  uint64_t* anc;
+  float* attn;  // bf16 attention partials
+};
+struct StepWs {
+  TreeWs t;
+  float2* cs;
+  float *x, *logits;
+  // bf16 mode
+  uint16_t *hp, *q, *op, *act;
+  float* partial;
+  // fp32 mode
+  float *h, *qkv, *qf, *of, *gu, *actf;
+};
+
+static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int max_seq_slots,
+                       TreeWs* w) {
+  w->depth = c.take<int32_t>(T);
+  w->row_slot = c.take<int32_t>(T);
+  w->row_pos = c.take<int32_t>(T);
+  w->row_seq = c.take<int32_t>(T);
+  w->status = c.take<int32_t>(B);
+  w->anc = c.take<uint64_t>(2 * (size_t)T);
+  w->attn = nullptr;
+  if (dtype == TRJ_BF16) {
+    int nqt, qg, bpw, ns;
+    attn_bf16_plan(B, T, H, max_seq_slots, &nqt, &qg, &bpw, &ns);
+    w->attn = c.take<float>(attn_bf16_ws_floats(T, H, dh, ns));
+  }
+}
+
+static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max_seq_slots,
+                       bool need_logits, StepWs* w) {
+  const int d = m.d_model, hd = m.n_heads * m.head_dim, F = m.d_ffn;
+  carve_tree(c, m.dtype, B, T, m.n_heads, m.head_dim, max_seq_slots, &w->t);
+  w->cs = c.take<float2>((size_t)T * (m.head_dim / 2));
+  w->x = c.take<float>((size_t)T * d);
+  w->logits = need_logits ? c.take<float>((size_t)T * m.vocab) : nullptr;
+  if (m.dtype == TRJ_BF16) {
+    const int tp = padded_rows(T);
+    w->hp = c.take<uint16_t>((size_t)tp * d);
+    w->q = c.take<uint16_t>((size_t)T * hd);
+    w->op = c.take<uint16_t>((size_t)tp * hd);
+    w->act = c.take<uint16_t>((size_t)tp * F);
+    int sk1 = gemm_bf16_split_k(d, tp, hd), sk2 = gemm_bf16_split_k(d, tp, F);
+    w->partial = c.take<float>((size_t)(sk1 > sk2 ? sk1 : sk2) * T * d);
+  } else {
+    w->h = c.take<float>((size_t)T * d);
+    w->qkv = c.take<float>((size_t)T * 3 * hd);
+    w->qf = c.take<float>((size_t)T * hd);
+    w->of = c.take<float>((size_t)T * hd);
+    w->gu = c.take<float>((size_t)T * 2 * F);
+    w->actf = c.take<float>((size_t)T * F);
+  }
+}
+
+static int check_desc(const trj_model_desc* m) {
+  if (!m) return TRJ_ERR_NULLPTR;
+  if (m->dtype != TRJ_F32 && m->dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (m->n_layers < 1 || m->d_model < 16 || m->n_heads < 1 || m->head_dim < 32 || m->d_ffn < 16 ||
+      m->vocab < 32)
+    return TRJ_ERR_BAD_SHAPE;
+  if ((m->d_model & 15) || (m->head_dim & 31) || (m->d_ffn & 15) || (m->vocab & 31))
+    return TRJ_ERR_BAD_SHAPE;
+  if (m->dtype == TRJ_BF16 && m->head_dim != 64 && m->head_dim != 128) return TRJ_ERR_BAD_SHAPE;
+  if (m->dtype == TRJ_BF16 && m->d_model > 8192) return TRJ_ERR_BAD_SHAPE;
+  if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return TRJ_ERR_BAD_SHAPE;
+  return TRJ_OK;
+}
+
+static int check_batch(int B, int T, int s_pool, int max_seq_slots) {
+  if (B < 1 || T < 1 || s_pool < TRJ_KV_BLOCK || (s_pool & (TRJ_KV_BLOCK - 1)))
+    return TRJ_ERR_BAD_SHAPE;
+  if (T < B) return TRJ_ERR_BAD_SHAPE;
+  if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  if (max_seq_slots < 1 || max_seq_slots > s_pool) return TRJ_ERR_BAD_SHAPE;
+  return TRJ_OK;
+}
+
+#define TRJ_TRY(expr)          \
+  do {                         \
+    int rc_ = (expr);          \
+    if (rc_ != TRJ_OK) return rc_; \
+  } while (0)
+
+}  // namespace trj
+
+using namespace trj;
+
+extern "C" {
+
+const char* trj_version(void) { return "trjacobi 0.1 (gfx950)"; }
+int32_t trj_last_hip_error(void) { return g_last_hip_error.load(); }
+
+// Tuning knobs for experiments (not part of the documented interface).
+int32_t trj_set_tunable(const char* name, int32_t value) {
+  if (!name) return TRJ_ERR_NULLPTR;
+  if (!strcmp(name, "gemm_target_wgs")) g_tune.gemm_target_wgs = value;
+  else if (!strcmp(name, "max_split_k")) g_tune.max_split_k = value;
+  else if (!strcmp(name, "attn_target_waves")) g_tune.attn_target_waves = value;
+  else if (!strcmp(name, "attn_min_bpw")) g_tune.attn_min_bpw = value;
+  else return TRJ_ERR_BAD_SHAPE;
+  return TRJ_OK;
+}
+
+int32_t trj_workspace_bytes(const trj_model_desc* desc, int32_t t_max, int32_t b_max,
+                            int32_t l_max, size_t* h_bytes) {
+  if (!h_bytes) return TRJ_ERR_NULLPTR;
+  TRJ_TRY(check_desc(desc));
+  if (t_max < 1 || b_max < 1 || l_max < 1) return TRJ_ERR_BAD_SHAPE;
+  Carver c(nullptr);
+  StepWs w;
+  carve_step(c, *desc, b_max, t_max, l_max, true, &w);
+  *h_bytes = align_up(c.off, 256);
+  return TRJ_OK;
+}
+
+int32_t trj_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, int32_t dtype,
+                        int32_t kind, int32_t n_heads, int32_t head_dim, void* stream) {
+  if (!dst || !src) return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (n_out < 32 || n_in < 16 || (n_out & 31) || (n_in & 15)) return TRJ_ERR_BAD_SHAPE;
+  if (kind == TRJ_PACK_QKV) {
+    if (n_heads < 1 || head_dim < 32 || (head_dim & 31) || n_out != 3 * n_heads * head_dim)
+      return TRJ_ERR_BAD_SHAPE;
+  } else if (kind == TRJ_PACK_GATE_UP) {
+    if (n_out & 63) return TRJ_ERR_BAD_SHAPE;
+  } else if (kind != TRJ_PACK_PLAIN) {
+    return TRJ_ERR_BAD_SHAPE;
+  }
+  return launch_pack_weight(dst, src, n_out, n_in, dtype, kind, n_heads, head_dim,
+                            (hipStream_t)stream);
+}
+
+static int kv_convert(void* k_pool, void* v_pool, void* k_plain, void* v_plain, int n_heads,
+                      int head_dim, int s_pool, int slot0, int n_slots, int dtype, bool pack,
+                      void* stream) {
+  if (!k_pool || !v_pool || !k_plain || !v_plain) return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (n_heads < 1 || head_dim < 32 || (head_dim & 31) || s_pool < 32 || (s_pool & 31) ||
+      slot0 < 0 || n_slots < 0 || (long)slot0 + n_slots > s_pool)
+    return TRJ_ERR_BAD_SHAPE;
+  return launch_kv_convert(k_pool, v_pool, k_plain, v_plain, n_heads, head_dim, s_pool, slot0,
+                           n_slots, dtype, pack, (hipStream_t)stream);
+}
+int32_t trj_kv_pack(void* k_pool, void* v_pool, const void* k_plain, const void* v_plain,
+                    int32_t n_heads, int32_t head_dim, int32_t s_pool, int32_t slot0,
+                    int32_t n_slots, int32_t dtype, void* stream) {
+  return kv_convert(k_pool, v_pool, const_cast<void*>(k_plain), const_cast<void*>(v_plain),
+                    n_heads, head_dim, s_pool, slot0, n_slots, dtype, true, stream);
+}
+int32_t trj_kv_unpack(void* k_plain, void* v_plain, const void* k_pool, const void* v_pool,
+                      int32_t n_heads, int32_t head_dim, int32_t s_pool, int32_t slot0,
+                      int32_t n_slots, int32_t dtype, void* stream) {
+  return kv_convert(const_cast<void*>(k_pool), const_cast<void*>(v_pool), k_plain, v_plain,
+                    n_heads, head_dim, s_pool, slot0, n_slots, dtype, false, stream);
+}
+
+int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B, int32_t T,
+                      int32_t* depth, uint64_t* anc, int32_t* status_dev, void* stream) {
+  if (!parent || !node_off || !depth || !anc || !status_dev) return TRJ_ERR_NULLPTR;
+  if (B < 1 || T < 1 || T < B) return TRJ_ERR_BAD_SHAPE;
+  if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  return launch_tree_prep(parent, node_off, nullptr, nullptr, B, T, 0, depth, anc, status_dev,
+                          nullptr, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
+                       const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                       const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
+                       int32_t head_dim, int32_t s_pool, int32_t max_seq_slots, int32_t dtype,
+                       float scale, void* workspace, size_t ws_bytes, void* out, void* stream) {
+  if (!q || !k_layer || !v_layer || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
+      !out)
+    return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  TRJ_TRY(check_batch(B, T, s_pool, max_seq_slots));
+  if (n_heads < 1 || head_dim < 32 || (head_dim & 31)) return TRJ_ERR_BAD_SHAPE;
+  if (dtype == TRJ_BF16 && head_dim != 64 && head_dim != 128) return TRJ_ERR_BAD_SHAPE;
+  if (dtype == TRJ_F32 && (size_t)(head_dim + max_seq_slots) * 4 > 64 * 1024)
+    return TRJ_ERR_BAD_SHAPE;
+  if (!(scale > 0.f)) return TRJ_ERR_BAD_SHAPE;
+  Carver c(workspace);
+  TreeWs w;
+  carve_tree(c, dtype, B, T, n_heads, head_dim, max_seq_slots, &w);
+  if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, w.depth, w.anc,
+                           w.status, w.row_slot, w.row_pos, w.row_seq, st));
+  if (dtype == TRJ_BF16)
+    return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
+                                 (const uint16_t*)v_layer, w.anc, w.row_seq, node_off, kv_off,
+                                 prefix_len, w.status, B, T, n_heads, head_dim, s_pool,
+                                 max_seq_slots, scale, w.attn, 0, 0, (uint16_t*)out, st);
+  return launch_tree_attn_f32((const float*)q, (const float*)k_layer, (const float*)v_layer, w.anc,
+                              w.row_seq, node_off, kv_off, prefix_len, w.status, T, n_heads,
+                              head_dim, s_pool, max_seq_slots, scale, (float*)out, st);
+}
+
+int32_t accept_path(const float* logits, const int32_t* tok, const int32_t* parent,
+                    const int32_t* node_off, int32_t B, int32_t T, int32_t V, int32_t* argmax_out,
+                    int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
+                    int32_t* status_dev, void* stream) {
+  if (!tok || !parent || !node_off || !argmax_out || !accept_len || !best_node || !path ||
+      !bonus_tok || !status_dev)
+    return TRJ_ERR_NULLPTR;
+  if (B < 1 || T < 1 || T < B || (logits && V < 1)) return TRJ_ERR_BAD_SHAPE;
+  if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  hipStream_t st = (hipStream_t)stream;
+  if (logits) TRJ_TRY(launch_argmax(logits, T, V, argmax_out, st));
+  return launch_accept(argmax_out, tok, parent, node_off, nullptr, B, T, accept_len, best_node,
+                       path, bonus_tok, status_dev, st);
+}
+
+int32_t kv_compact(void* k_pool, void* v_pool, size_t kv_layer_stride, const int32_t* path,
+                   const int32_t* accept_len, const int32_t* kv_off, const int32_t* prefix_len,
+                   int32_t B, int32_t n_layers, int32_t n_heads, int32_t head_dim, int32_t s_pool,
+                   int32_t dtype, int32_t* new_len, void* stream) {
+  if (!k_pool || !v_pool || !path || !accept_len || !kv_off || !prefix_len || !new_len)
+    return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (B < 1 || n_layers < 1 || n_heads < 1 || head_dim < 32 || (head_dim & 31) || s_pool < 32 ||
+      (s_pool & 31) || kv_layer_stride < (size_t)n_heads * s_pool * head_dim)
+    return TRJ_ERR_BAD_SHAPE;
+  if ((long)n_layers * n_heads > 65535) return TRJ_ERR_BAD_SHAPE;
+  return launch_kv_compact(k_pool, v_pool, kv_layer_stride, path, accept_len, kv_off, prefix_len,
+                           B, n_layers, n_heads, head_dim, s_pool, dtype, new_len,
+                           (hipStream_t)stream);
+}
+
+// y[T][n_out] (fp32) = x[T][n_in] * W^T for a TRJ_PACK_PLAIN weight; x plain row-major in
+// `dtype`.  Exposes the projection kernel alone (tests, roofline measurements).
+// split_k <= 0 picks the library's choice.
+int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in, int32_t n_out,
+                   int32_t dtype, int32_t split_k, void* workspace, size_t ws_bytes, float* y,
+                   void* stream) {
+  if (!x || !w_packed || !y || !workspace) return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (T < 1 || n_in < 16 || n_out < 32 || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == TRJ_F32)
+    return launch_gemm_f32((const float*)x, (const float*)w_packed, T, n_in, n_out, 0, y, st);
+  const int tp = padded_rows(T);
+  int sk = split_k > 0 ? split_k : gemm_bf16_split_k(n_out, tp, n_in);
+  Carver c(workspace);
+  uint16_t* xp = c.take<uint16_t>((size_t)tp * n_in);
+  float* part = c.take<float>((size_t)sk * T * n_out);
+  if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
+  TRJ_TRY(launch_tile_activation((const uint16_t*)x, T, n_in, tp, xp, st));
+  if (sk == 1) return launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, 1, y, st);
+  TRJ_TRY(launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, sk, part, st));
+  return launch_sum_splits(part, sk, (size_t)T * n_out, y, st);
+}
+
+int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
+                       void* v_pool, size_t kv_layer_stride, int32_t s_pool, const int32_t* tok,
+                       const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                       const int32_t* prefix_len, int32_t B, int32_t T, int32_t max_seq_slots,
+                       void* workspace, size_t ws_bytes, float* logits, int32_t* argmax_out,
+                       int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
+                       int32_t* new_len, int32_t* status_dev, void* stream) {
+  TRJ_TRY(check_desc(desc));
+  if (!weights || !weights->h_layers || !weights->embed || !weights->g_final || !weights->w_lm ||
+      !k_pool || !v_pool || !tok || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
+      !argmax_out || !accept_len || !best_node || !path || !bonus_tok || !new_len || !status_dev)
+    return TRJ_ERR_NULLPTR;
+  const trj_model_desc& m = *desc;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const trj_layer_weights& lw = weights->h_layers[l];
+    if (!lw.g_attn || !lw.wqkv || !lw.wo || !lw.g_ffn || !lw.w_gate_up || !lw.w_down)
+      return TRJ_ERR_NULLPTR;
+  }
+  TRJ_TRY(check_batch(B, T, s_pool, max_seq_slots));
+  const int d = m.d_model, H = m.n_heads, dh = m.head_dim, hd = H * dh, F = m.d_ffn, V = m.vocab;
+  if (kv_layer_stride < (size_t)H * s_pool * dh || (long)m.n_layers * H > 65535)
+    return TRJ_ERR_BAD_SHAPE;
+  if (m.dtype == TRJ_F32 && (size_t)(dh + max_seq_slots) * 4 > 64 * 1024) return TRJ_ERR_BAD_SHAPE;
+
+  Carver c(workspace);
+  StepWs w;
+  carve_step(c, m, B, T, max_seq_slots, logits == nullptr, &w);
+  if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
+  float* lg = logits ? logits : w.logits;
+  hipStream_t st = (hipStream_t)stream;
+  const float scale = 1.0f / sqrtf((float)dh);
+
+  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, w.t.depth, w.t.anc,
+                           status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq, st));
+  TRJ_TRY(launch_rope_table(w.t.row_pos, T, dh, m.rope_theta, w.cs, st));
+  TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
+
+  if (m.dtype == TRJ_BF16) {
+    const int tp = padded_rows(T);
+    const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
+    TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
+                               w.hp, st));
+    for (int l = 0; l < m.n_layers; ++l) {
+      const trj_layer_weights& lw = weights->h_layers[l];
+      uint16_t* kl = (uint16_t*)k_pool + (size_t)l * kv_layer_stride;
+      uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
+      TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
+                              w.t.row_slot, w.q, kl, vl, st));
+      TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off,
+                                    prefix_len, status_dev, B, T, H, dh, s_pool, max_seq_slots,
+                                    scale, w.t.attn, 1, tp, w.op, st));
+      TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st));
+      TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st));
+      TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st));
+      TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, w.partial, st));
+      const float* g_next = l + 1 < m.n_layers ? weights->h_layers[l + 1].g_attn : weights->g_final;
+      TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st));
+    }
+    TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st));
+  } else {
+    for (int l = 0; l < m.n_layers; ++l) {
+      const trj_layer_weights& lw = weights->h_layers[l];
+      float* kl = (float*)k_pool + (size_t)l * kv_layer_stride;
+      float* vl = (float*)v_pool + (size_t)l * kv_layer_stride;
+      TRJ_TRY(launch_rmsnorm_f32(w.x, lw.g_attn, T, d, m.rms_eps, w.h, st));
+      TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.wqkv, T, d, 3 * hd, 0, w.qkv, st));
+      TRJ_TRY(launch_rope_kv_f32(w.qkv, w.cs, w.t.row_slot, T, H, dh, s_pool, w.qf, kl, vl, st));
+      TRJ_TRY(launch_tree_attn_f32(w.qf, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off, prefix_len,
+                                   status_dev, T, H, dh, s_pool, max_seq_slots, scale, w.of, st));
+      TRJ_TRY(launch_gemm_f32(w.of, (const float*)lw.wo, T, hd, d, 1, w.x, st));
+      TRJ_TRY(launch_rmsnorm_f32(w.x, lw.g_ffn, T, d, m.rms_eps, w.h, st));
+      TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.w_gate_up, T, d, 2 * F, 0, w.gu, st));
+      TRJ_TRY(launch_silu_mul_f32(w.gu, T, F, w.actf, st));
+      TRJ_TRY(launch_gemm_f32(w.actf, (const float*)lw.w_down, T, F, d, 1, w.x, st));
+    }
+    TRJ_TRY(launch_rmsnorm_f32(w.x, weights->g_final, T, d, m.rms_eps, w.h, st));
+    TRJ_TRY(launch_gemm_f32(w.h, (const float*)weights->w_lm, T, d, V, 0, lg, st));
+  }
+  TRJ_TRY(launch_argmax(lg, T, V, argmax_out, st));
+  TRJ_TRY(launch_accept(argmax_out, tok, parent, node_off, status_dev, B, T, accept_len, best_node,
+                        path, bonus_tok, status_dev, st));
+  return launch_kv_compact(k_pool, v_pool, kv_layer_stride, path, accept_len, kv_off, prefix_len, B,
+                           m.n_layers, H, dh, s_pool, m.dtype, new_len, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Internal launcher declarations shared by the .hip files.  Every launcher only
+// enqueues on the given stream and returns a trj_status.
+#pragma once
+#include "common.h"
+
+namespace trj {
+
+struct Tunables {
+  int gemm_target_wgs = 256;   // split-k is raised until a GEMM has this many workgroups
+  int max_split_k = 8;
+  int attn_target_waves = 1024;
+  int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
+};
+extern Tunables g_tune;
+
+// tree_kernels.hip
+int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                     const int32_t* prefix_len, int B, int T, int s_pool, int32_t* depth,
+                     uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
+                     int32_t* row_seq, hipStream_t st);
+int launch_argmax(const float* logits, int T, int V, int32_t* out, hipStream_t st);
+int launch_accept(const int32_t* argmax, const int32_t* tok, const int32_t* parent,
+                  const int32_t* node_off, const int32_t* status_in, int B, int T,
+                  int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
+                  int32_t* status_dev, hipStream_t st);
+int launch_kv_compact(void* k_pool, void* v_pool, size_t layer_stride, const int32_t* path,
+                      const int32_t* accept_len, const int32_t* kv_off, const int32_t* prefix_len,
+                      int B, int n_layers, int n_heads, int dh, int s_pool, int dtype,
+                      int32_t* new_len, hipStream_t st);
+int launch_kv_convert(void* k_pool, void* v_pool, void* k_plain, void* v_plain, int n_heads,
+                      int dh, int s_pool, int slot0, int n_slots, int dtype, bool pack,
+                      hipStream_t st);
+int launch_pack_weight(void* dst, const void* src, int n_out, int n_in, int dtype, int kind,
+                       int n_heads, int dh, hipStream_t st);
+
+// f32_kernels.hip
+int launch_rope_table(const int32_t* row_pos, int T, int dh, float theta, float2* cs,
+                      hipStream_t st);
+int launch_embed(const void* embed, const int32_t* tok, int T, int d, int vocab, int dtype,
+                 float* x, hipStream_t st);
+int launch_rmsnorm_f32(const float* x, const float* g, int T, int d, float eps, float* h,
+                       hipStream_t st);
+int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, int add_to,
+                    float* y, hipStream_t st);
+int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* row_slot, int T,
+                       int n_heads, int dh, int s_pool, float* q, float* k_layer, float* v_layer,
+                       hipStream_t st);
+int launch_silu_mul_f32(const float* gu, int T, int F, float* act, hipStream_t st);
+int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_layer,
+                         const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
+                         const int32_t* kv_off, const int32_t* prefix_len,
+                         const int32_t* status_dev, int T, int n_heads, int dh, int s_pool,
+                         int max_slots, float scale, float* out, hipStream_t st);
+
+// gemm_bf16.hip
+int gemm_bf16_split_k(int n_out, int tp, int n_in);
+int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
+                          int n_out, int split_k, float* y, hipStream_t st);
+int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
+                        uint16_t* act, hipStream_t st);
+int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
+                    int dh, int s_pool, const float2* cs, const int32_t* row_slot, uint16_t* q,
+                    uint16_t* k_layer, uint16_t* v_layer, hipStream_t st);
+int launch_reduce_norm(const float* partial, int n_split, float* x, const float* g, int T, int d,
+                       int tp, float eps, uint16_t* hp, hipStream_t st);
+int launch_sum_splits(const float* partial, int n_split, size_t n, float* y, hipStream_t st);
+int launch_tile_activation(const uint16_t* x, int T, int n, int tp, uint16_t* xp, hipStream_t st);
+
+// attn_bf16.hip
+void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* nqt, int* qg_max, int* bpw,
+                    int* nsplit_max);
+size_t attn_bf16_ws_floats(int T, int n_heads, int dh, int nsplit_max);
+int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
+                          const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
+                          const int32_t* kv_off, const int32_t* prefix_len,
+                          const int32_t* status_dev, int B, int T, int n_heads, int dh, int s_pool,
+                          int max_seq_slots, float scale, float* ws, int tiled, int tp,
+                          uint16_t* out, hipStream_t st);
+
+inline int padded_rows(int T) { return T <= 32 ? 32 : (T <= 64 ? 64 : (T + 127) / 128 * 128); }
+
+}  // namespace trj

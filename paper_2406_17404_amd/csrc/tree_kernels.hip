@@ -1,0 +1,335 @@
+// Integer / byte kernels of the verify step: tree bookkeeping (depth, ancestor bit
+// rows), greedy argmax, longest accepted path, KV compaction, and the layout
+// converters.  All results here are exact (no floating point decides anything except
+// the comparisons inside argmax).
+#include "common.h"
+#include "kernels.h"
+
+namespace trj {
+
+// ------------------------------------------------------------------ tree bookkeeping
+// One workgroup of TRJ_N_MAX threads per sequence.  A tree is well formed when
+// parent[0] == -1 and 0 <= parent[i] < i; then walking parents strictly decreases the
+// index, so every walk ends at the root.  When the KV arrays are given, the sequence's
+// slot range must also lie inside the pool and start on a block boundary.  Rows of a
+// malformed sequence get depth 0, empty bit rows and row_slot -1, which makes every
+// later kernel skip them.
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+__global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ node_off,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ prefix_len, int T, int s_pool,
+    int32_t* __restrict__ depth, uint64_t* __restrict__ anc, int32_t* __restrict__ status_dev,
+    int32_t* __restrict__ row_slot, int32_t* __restrict__ row_pos, int32_t* __restrict__ row_seq) {
+  __shared__ int32_t par[TRJ_N_MAX];
+  __shared__ int32_t bad;
+  const int s = blockIdx.x, i = threadIdx.x;
+  int r0 = node_off[s], r1 = node_off[s + 1];
+  // row range must lie inside [0, T] and hold 1..TRJ_N_MAX rows
+  bool range_ok = r0 >= 0 && r1 <= T && r1 > r0 && (r1 - r0) <= TRJ_N_MAX;
+  int n = range_ok ? r1 - r0 : 0;
+  if (i == 0) {
+    int b = range_ok ? 0 : 1;
+    if (kv_off && range_ok) {
+      int ko = kv_off[s], L = prefix_len[s];
+      if (ko < 0 || (ko & (TRJ_KV_BLOCK - 1)) || L < 0 || (long)ko + L + n > (long)s_pool) b = 1;
+    }
+    bad = b;
+  }
+  __syncthreads();
+  if (i < n) {
+    int p = parent[r0 + i];
+    par[i] = p;
+    if (i == 0 ? p != -1 : (p < 0 || p >= i)) atomicOr(&bad, 1);
+  }
+  __syncthreads();
+  const int is_bad = bad;
+  if (i == 0) status_dev[s] = is_bad;
+  if (i >= n) return;  // nothing is written outside a valid row range
+  uint64_t lo = 0, hi = 0;
+  int d = 0;
+  if (!is_bad) {
+    d = -1;
+    for (int j = i; j >= 0; j = par[j]) {
+      if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
+      ++d;
+    }
+  }
+  depth[r0 + i] = d;
+  anc[2 * (size_t)(r0 + i)] = lo;
+  anc[2 * (size_t)(r0 + i) + 1] = hi;
+  if (row_slot) {
+    int L = prefix_len[s];
+    row_slot[r0 + i] = is_bad ? -1 : kv_off[s] + L + i;
+    row_pos[r0 + i] = is_bad ? 0 : L + d;
+    row_seq[r0 + i] = is_bad ? -1 : s;
+  }
+}
+
+int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                     const int32_t* prefix_len, int B, int T, int s_pool, int32_t* depth,
+                     uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
+                     int32_t* row_seq, hipStream_t st) {
+  // rows that no valid sequence covers must read as "skip"
+  int nb = (T + 255) / 256;
+  fill_i32_kernel<<<nb, 256, 0, st>>>(depth, 0, T);
+  fill_i32_kernel<<<(4 * T + 255) / 256, 256, 0, st>>>(reinterpret_cast<int32_t*>(anc), 0, 4 * T);
+  if (row_slot) {
+    fill_i32_kernel<<<nb, 256, 0, st>>>(row_slot, -1, T);
+    fill_i32_kernel<<<nb, 256, 0, st>>>(row_pos, 0, T);
+    fill_i32_kernel<<<nb, 256, 0, st>>>(row_seq, -1, T);
+  }
+  tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool, depth,
+                                            anc, status_dev, row_slot, row_pos, row_seq);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ greedy argmax
+// One workgroup per row; lowest index wins ties; NaN never compares greater.
+constexpr int ARGMAX_THREADS = 256;
+__device__ inline void amax_merge(float& bv, int& bi, float v, int i) {
+  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+__global__ __launch_bounds__(ARGMAX_THREADS) void argmax_kernel(const float* __restrict__ logits,
+                                                                int V, int32_t* __restrict__ out) {
+  const float* row = logits + (size_t)blockIdx.x * V;
+  float bv = -INFINITY;
+  int bi = INT32_MAX;
+  const int tid = threadIdx.x;
+  if ((V & 3) == 0 && (((uintptr_t)row) & 15) == 0) {
+    const float4* r4 = reinterpret_cast<const float4*>(row);
+    for (int i = tid; i < (V >> 2); i += ARGMAX_THREADS) {
+      float4 x = r4[i];
+      amax_merge(bv, bi, x.x, 4 * i);
+      amax_merge(bv, bi, x.y, 4 * i + 1);
+      amax_merge(bv, bi, x.z, 4 * i + 2);
+      amax_merge(bv, bi, x.w, 4 * i + 3);
+    }
+  } else {
+    for (int i = tid; i < V; i += ARGMAX_THREADS) amax_merge(bv, bi, row[i], i);
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(bv, o);
+    int oi = __shfl_xor(bi, o);
+    amax_merge(bv, bi, ov, oi);
+  }
+  __shared__ float sv[ARGMAX_THREADS / WAVE];
+  __shared__ int si[ARGMAX_THREADS / WAVE];
+  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < ARGMAX_THREADS / WAVE; ++w) amax_merge(bv, bi, sv[w], si[w]);
+    out[blockIdx.x] = bi == INT32_MAX ? 0 : bi;
+  }
+}
+
+int launch_argmax(const float* logits, int T, int V, int32_t* out, hipStream_t st) {
+  argmax_kernel<<<T, ARGMAX_THREADS, 0, st>>>(logits, V, out);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ accept
+// One workgroup of TRJ_N_MAX threads per sequence.  ok[i] is evaluated by walking from
+// i to the root; best = max over ok nodes of (depth, -index).  status_in (optional)
+// marks sequences an earlier kernel already found malformed.
+__global__ __launch_bounds__(TRJ_N_MAX) void accept_kernel(
+    const int32_t* __restrict__ argmax, const int32_t* __restrict__ tok,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ node_off, int T,
+    const int32_t* status_in, int32_t* __restrict__ accept_len,
+    int32_t* __restrict__ best_node, int32_t* __restrict__ path, int32_t* __restrict__ bonus_tok,
+    int32_t* status_dev) {  // status_in may alias status_dev
+  __shared__ int32_t par[TRJ_N_MAX], tk[TRJ_N_MAX], am[TRJ_N_MAX];
+  __shared__ int32_t bad, best_key;
+  const int s = blockIdx.x, i = threadIdx.x;
+  int r0 = node_off[s], r1 = node_off[s + 1];
+  bool range_ok = r0 >= 0 && r1 <= T && r1 > r0 && (r1 - r0) <= TRJ_N_MAX;
+  int n = range_ok ? r1 - r0 : 0;
+  if (i == 0) {
+    bad = (range_ok && !(status_in && status_in[s] != 0)) ? 0 : 1;
+    best_key = -1;
+  }
+  __syncthreads();
+  if (i < n) {
+    int p = parent[r0 + i];
+    par[i] = p;
+    tk[i] = tok[r0 + i];
+    am[i] = argmax[r0 + i];
+    if (i == 0 ? p != -1 : (p < 0 || p >= i)) atomicOr(&bad, 1);
+  }
+  __syncthreads();
+  int32_t* my_path = path + (size_t)s * TRJ_N_MAX;
+  my_path[i] = -1;
+  if (bad) {
+    if (i == 0) {
+      status_dev[s] = 1;
+      accept_len[s] = -1;
+      best_node[s] = -1;
+      bonus_tok[s] = -1;
+    }
+    return;
+  }
+  if (i < n) {
+    bool ok = true;
+    int d = 0;
+    for (int j = i; j > 0; j = par[j]) {
+      ok = ok && (tk[j] == am[par[j]]);
+      ++d;
+    }
+    if (ok) atomicMax(&best_key, (d << 8) | (255 - i));
+  }
+  __syncthreads();  // also orders the -1 fill above before the path writes below
+  if (i == 0) {
+    int key = best_key;  // the root is always ok, so key >= 255
+    int b = 255 - (key & 255), d = key >> 8;
+    status_dev[s] = 0;
+    accept_len[s] = d;
+    best_node[s] = b;
+    bonus_tok[s] = am[b];
+    for (int j = b, k = d; j >= 0; j = par[j], --k) my_path[k] = j;
+  }
+}
+
+int launch_accept(const int32_t* argmax, const int32_t* tok, const int32_t* parent,
+                  const int32_t* node_off, const int32_t* status_in, int B, int T,
+                  int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
+                  int32_t* status_dev, hipStream_t st) {
+  accept_kernel<<<B, TRJ_N_MAX, 0, st>>>(argmax, tok, parent, node_off, T, status_in, accept_len,
+                                         best_node, path, bonus_tok, status_dev);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ KV compaction
+// One workgroup per (sequence, layer*head) plane, one thread per head_dim column.
+// Row j of the accepted path moves from slot base+path[j] to base+j.  path is
+// increasing with path[j] >= j, so copying in increasing j with a barrier between rows
+// never overwrites a row that is still to be read.
+template <typename E>
+__global__ void kv_compact_kernel(E* __restrict__ k_pool, E* __restrict__ v_pool,
+                                  size_t layer_stride, const int32_t* __restrict__ path,
+                                  const int32_t* __restrict__ accept_len,
+                                  const int32_t* __restrict__ kv_off,
+                                  const int32_t* __restrict__ prefix_len, int n_heads, int dh,
+                                  int s_pool, int32_t* __restrict__ new_len) {
+  const int s = blockIdx.x, plane = blockIdx.y;
+  const int layer = plane / n_heads, head = plane % n_heads;
+  const int a = accept_len[s];
+  const int L = prefix_len[s];
+  if (plane == 0 && threadIdx.x == 0) new_len[s] = a < 0 ? L : L + a + 1;
+  if (a < 0) return;
+  const int base = kv_off[s] + L;
+  E* kp = k_pool + layer * layer_stride + (size_t)head * s_pool * dh;
+  E* vp = v_pool + layer * layer_stride + (size_t)head * s_pool * dh;
+  const int32_t* pth = path + (size_t)s * TRJ_N_MAX;
+  for (int j = 0; j <= a && j < TRJ_N_MAX; ++j) {
+    int src = pth[j];
+    if (src > j && src < TRJ_N_MAX && base + src < s_pool) {  // uniform over the workgroup
+      for (int c = threadIdx.x; c < dh; c += blockDim.x) {
+        E kk = kp[k_off(base + src, c, dh)];
+        E vv = vp[v_off(base + src, c, dh)];
+        kp[k_off(base + j, c, dh)] = kk;
+        vp[v_off(base + j, c, dh)] = vv;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+int launch_kv_compact(void* k_pool, void* v_pool, size_t layer_stride, const int32_t* path,
+                      const int32_t* accept_len, const int32_t* kv_off, const int32_t* prefix_len,
+                      int B, int n_layers, int n_heads, int dh, int s_pool, int dtype,
+                      int32_t* new_len, hipStream_t st) {
+  dim3 grid(B, n_layers * n_heads);
+  int threads = dh < 64 ? 64 : (dh > 256 ? 256 : dh);
+  if (dtype == TRJ_BF16)
+    kv_compact_kernel<uint16_t><<<grid, threads, 0, st>>>((uint16_t*)k_pool, (uint16_t*)v_pool,
+                                                          layer_stride, path, accept_len, kv_off,
+                                                          prefix_len, n_heads, dh, s_pool, new_len);
+  else
+    kv_compact_kernel<uint32_t><<<grid, threads, 0, st>>>((uint32_t*)k_pool, (uint32_t*)v_pool,
+                                                          layer_stride, path, accept_len, kv_off,
+                                                          prefix_len, n_heads, dh, s_pool, new_len);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ layout converters
+template <typename E, bool PACK>
+__global__ void kv_convert_kernel(E* __restrict__ k_pool, E* __restrict__ v_pool,
+                                  E* __restrict__ k_plain, E* __restrict__ v_plain, int dh,
+                                  int s_pool, int slot0, int n_slots) {
+  const int head = blockIdx.y;
+  size_t total = (size_t)n_slots * dh;
+  E* kp = k_pool + (size_t)head * s_pool * dh;
+  E* vp = v_pool + (size_t)head * s_pool * dh;
+  E* kl = k_plain + (size_t)head * n_slots * dh;
+  E* vl = v_plain + (size_t)head * n_slots * dh;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    int sl = (int)(i / dh), c = (int)(i % dh);
+    if (PACK) {
+      kp[k_off(slot0 + sl, c, dh)] = kl[i];
+      vp[v_off(slot0 + sl, c, dh)] = vl[i];
+    } else {
+      kl[i] = kp[k_off(slot0 + sl, c, dh)];
+      vl[i] = vp[v_off(slot0 + sl, c, dh)];
+    }
+  }
+}
+
+int launch_kv_convert(void* k_pool, void* v_pool, void* k_plain, void* v_plain, int n_heads,
+                      int dh, int s_pool, int slot0, int n_slots, int dtype, bool pack,
+                      hipStream_t st) {
+  if (n_slots == 0) return TRJ_OK;
+  size_t total = (size_t)n_slots * dh;
+  int bx = (int)((total + 255) / 256);
+  if (bx > 1024) bx = 1024;
+  dim3 grid(bx, n_heads);
+#define TRJ_KVC(E, P)                                                                         \
+  kv_convert_kernel<E, P><<<grid, 256, 0, st>>>((E*)k_pool, (E*)v_pool, (E*)k_plain,          \
+                                                (E*)v_plain, dh, s_pool, slot0, n_slots)
+  if (dtype == TRJ_BF16) {
+    if (pack) TRJ_KVC(uint16_t, true); else TRJ_KVC(uint16_t, false);
+  } else {
+    if (pack) TRJ_KVC(uint32_t, true); else TRJ_KVC(uint32_t, false);
+  }
+#undef TRJ_KVC
+  return check_launch();
+}
+
+// one thread per 8-element granule of the packed matrix
+template <typename E>
+__global__ void pack_weight_kernel(E* __restrict__ dst, const E* __restrict__ src, int n_out,
+                                   int n_in, int kind, int n_heads, int dh) {
+  size_t granules = (size_t)n_out * (n_in >> 3);
+  for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < granules;
+       g += (size_t)gridDim.x * blockDim.x) {
+    // granule g of the packed buffer: decode (tile row, k-step, half, row in tile)
+    size_t tile = g >> 6;
+    int lane = (int)(g & 63);
+    int ksteps = n_in >> 4;
+    int rt = (int)(tile / ksteps), ks = (int)(tile % ksteps);
+    int r = rt * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
+    const E* s = src + (size_t)logical_row(r, kind, n_out, n_heads, dh) * n_in + k;
+    E* d = dst + g * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d[e] = s[e];
+  }
+}
+
+int launch_pack_weight(void* dst, const void* src, int n_out, int n_in, int dtype, int kind,
+                       int n_heads, int dh, hipStream_t st) {
+  size_t granules = (size_t)n_out * (n_in >> 3);
+  int bx = (int)((granules + 255) / 256);
+  if (bx > 65536) bx = 65536;
+  if (dtype == TRJ_BF16)
+    pack_weight_kernel<uint16_t><<<bx, 256, 0, st>>>((uint16_t*)dst, (const uint16_t*)src, n_out,
+                                                     n_in, kind, n_heads, dh);
+  else
+    pack_weight_kernel<uint32_t><<<bx, 256, 0, st>>>((uint32_t*)dst, (const uint32_t*)src, n_out,
+                                                     n_in, kind, n_heads, dh);
+  return check_launch();
+}
+
+}  // namespace trj

@@ -1,0 +1,48 @@
+"""The C-ABI library builds, loads without a GPU and exports every function that
+include/trjacobi.h declares; the Python binding knows the same names."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared():
+    text = open(os.path.join(ROOT, "include", "trjacobi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"^(?:int32_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = declared()
+    for n in ("tr_verify_step", "tree_attention", "accept_path", "kv_compact"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2406_17404_amd import binding
+    assert os.path.exists(binding.LIB_PATH), "build the library first (__graft_entry__.build())"
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in declared():
+        assert hasattr(lib, n), n
+    assert sorted(binding.exported_symbols()) == declared()
+
+
+def test_version_and_host_side_errors_need_no_gpu():
+    from paper_2406_17404_amd import binding as b
+    assert "gfx950" in b.trj_version()
+    l = b.lib()
+    # null pointers and bad shapes are rejected before anything touches a device
+    n = ctypes.c_size_t(0)
+    assert l.trj_workspace_bytes(None, 64, 1, 1088, ctypes.byref(n)) == -1
+    d = b.ModelDesc(2, 256, 4, 64, 1024, 2048, 1e-5, 1e4, b.F32)
+    assert l.trj_workspace_bytes(ctypes.byref(d), 15, 1, 143, ctypes.byref(n)) == 0 and n.value > 0
+    d.dtype = 7
+    assert l.trj_workspace_bytes(ctypes.byref(d), 15, 1, 143, ctypes.byref(n)) == -3
+    d.dtype, d.d_model = b.BF16, 250
+    assert l.trj_workspace_bytes(ctypes.byref(d), 15, 1, 143, ctypes.byref(n)) == -2
+    assert l.trj_tree_mask(None, None, 1, 1, None, None, None, None) == -1
+    assert l.accept_path(None, 1, 1, 1, 1, 1000, 8, 1, 1, 1, 1, 1, 1, None) == -4
+    assert l.kv_compact(None, None, 0, None, None, None, None, 1, 1, 1, 64, 64, 0, None, None) == -1

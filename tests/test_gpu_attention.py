@@ -1,0 +1,129 @@
+"""tree_attention through the C-ABI against the oracle on the same seeded inputs:
+relative error (max |gpu - oracle| / max |oracle|) at most 1e-5 in fp32 mode and 1e-2
+in bf16 mode (inputs are bf16-rounded once on the host and shared by both sides)."""
+import numpy as np
+import pytest
+import torch
+
+import layouts
+from gpu_util import DEV, Batch, rel_err, tdtype, to_dev
+from oracle import tr_oracle as O
+from paper_2406_17404_amd import binding as b
+from paper_2406_17404_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def run_attention(dtype, H, dh, cases, align=64, nan_fill=True, scale=None):
+    """cases: list of (q[n,H,dh], k[H,L+n,dh], v, parent, L).  Returns per-case outputs."""
+    trees = [c[3] for c in cases]
+    prefix = [c[4] for c in cases]
+    batch = Batch(trees, prefix, align=align)
+    fill = np.nan if nan_fill else 0.0
+    kp = np.full((H, batch.s_pool * dh), fill, np.float32)
+    vp = np.full((H, batch.s_pool * dh), fill, np.float32)
+    for s, (q, k, v, parent, L) in enumerate(cases):
+        layouts.kv_to_pool(k.astype(np.float32), v.astype(np.float32), batch.s_pool,
+                           int(batch.kv_off_h[s]), kp, vp)
+    dt = tdtype(dtype)
+    code = b.BF16 if dtype == "bf16" else b.F32
+    qd = to_dev(np.concatenate([c[0] for c in cases]).astype(np.float32), dt)
+    out = torch.full((batch.T, H, dh), float("nan"), dtype=dt, device=DEV)
+    desc = b.ModelDesc(1, 64, H, dh, 64, 64, 1e-5, 1e4, code)
+    ws = torch.empty(b.trj_workspace_bytes(desc, batch.T, batch.B, batch.max_seq_slots),
+                     dtype=torch.uint8, device=DEV)
+    sc = float(1.0 / np.sqrt(dh)) if scale is None else scale
+    b.tree_attention(qd, to_dev(kp, dt), to_dev(vp, dt), batch.parent, batch.node_off, batch.kv_off,
+                     batch.prefix, batch.B, batch.T, H, dh, batch.s_pool, batch.max_seq_slots, code,
+                     sc, ws, out)
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy()
+    return [o[batch.rows(s)] for s in range(batch.B)]
+
+
+def case(seed, H, dh, L, n, dtype, parent=None):
+    q, k, v, p = I.gen_attention_case(seed, H, dh, L, n, dtype)
+    return (q, k, v, p if parent is None else parent, L)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,dh,L,n", [
+    (4, 64, 128, 15),      # the tiny workload's shape
+    (2, 128, 0, 1),        # empty prefix, root only
+    (2, 128, 0, 33),       # empty prefix, tree spans two query tiles
+    (3, 128, 31, 64),      # tree straddles a block boundary
+    (2, 128, 500, 128),    # maximum tree, two query groups
+    (2, 64, 257, 100),     # ragged everything
+    (1, 128, 2048, 16),    # longer prefix, several splits
+])
+def test_single_sequence(dtype, H, dh, L, n):
+    c = case(7 * L + n, H, dh, L, n, dtype)
+    got = run_attention(dtype, H, dh, [c])[0]
+    want = O.tree_attention(*c)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chain_and_star_trees(dtype):
+    H, dh, L, n = 2, 128, 70, 40
+    star = np.array([-1] + [0] * (n - 1), np.int32)
+    for parent in (I.tree_chain(n), star, I.tree_c3(n, np.random.default_rng(0), chain=8)):
+        c = case(11, H, dh, L, n, dtype, parent)
+        got = run_attention(dtype, H, dh, [c])[0]
+        assert rel_err(got, O.tree_attention(*c)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_packed_ragged_batch(dtype):
+    H, dh = 4, 128
+    rng = np.random.default_rng(5)
+    cases = []
+    for s in range(6):
+        L, n = int(rng.integers(0, 700)), int(rng.integers(1, 129))
+        cases.append(case(100 + s, H, dh, L, n, dtype))
+    got = run_attention(dtype, H, dh, cases, align=32)
+    for g, c in zip(got, cases):
+        assert rel_err(g, O.tree_attention(*c)) <= TOL[dtype]
+
+
+def test_bf16_launch_shapes_give_the_same_answer():
+    """Different splits of the key range only change fp32 summation order."""
+    H, dh, L, n = 4, 128, 1500, 64
+    c = case(21, H, dh, L, n, "bf16")
+    want = O.tree_attention(*c)
+    try:
+        for waves, bpw in ((64, 1), (4096, 1), (1024, 7), (1, 1)):
+            b.trj_set_tunable("attn_target_waves", waves)
+            b.trj_set_tunable("attn_min_bpw", bpw)
+            got = run_attention("bf16", H, dh, [c])[0]
+            assert rel_err(got, want) <= 1e-2
+    finally:
+        b.trj_set_tunable("attn_target_waves", 1024)
+        b.trj_set_tunable("attn_min_bpw", 2)
+
+
+def test_malformed_sequence_is_skipped():
+    H, dh = 2, 128
+    good = case(1, H, dh, 40, 20, "bf16")
+    bad = case(2, H, dh, 10, 5, "bf16", parent=np.array([-1, 0, 2, 1, 0], np.int32))
+    got = run_attention("bf16", H, dh, [good, bad, good])
+    assert rel_err(got[0], O.tree_attention(*good)) <= 1e-2
+    assert rel_err(got[2], O.tree_attention(*good)) <= 1e-2
+    assert (got[1] == 0).all()
+
+
+def test_host_side_errors():
+    H, dh = 2, 128
+    c = case(1, H, dh, 40, 20, "bf16")
+    with pytest.raises(b.TrjError) as e:
+        run_attention("bf16", H, dh, [c], scale=-1.0)
+    assert e.value.status == -2
+    t = torch.zeros(64, dtype=torch.int32, device=DEV)
+    with pytest.raises(b.TrjError) as e:   # workspace too small
+        b.tree_attention(t, t, t, t, t, t, t, 1, 20, H, dh, 64, 60, b.BF16, 0.1, t[:4], t)
+    assert e.value.status == -5
+    with pytest.raises(b.TrjError) as e:   # more rows than B * N_MAX
+        b.tree_attention(t, t, t, t, t, t, t, 1, 129, H, dh, 64, 60, b.BF16, 0.1, t, t)
+    assert e.value.status == -4

@@ -1,0 +1,44 @@
+"""The projection kernel alone (trj_linear) against a plain fp64 matrix product."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import DEV, rel_err, tdtype, to_dev
+from paper_2406_17404_amd import binding as b
+from paper_2406_17404_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def run_linear(dtype, T, n_in, n_out, split_k, seed=0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, n_in)).astype(np.float32)
+    w = (rng.standard_normal((n_out, n_in)) * 0.05).astype(np.float32)
+    if dtype == "bf16":
+        x, w = I.bf16_round(x), I.bf16_round(w)
+    dt, code = tdtype(dtype), (b.BF16 if dtype == "bf16" else b.F32)
+    wd = to_dev(w, dt)
+    wp = torch.empty_like(wd)
+    b.trj_pack_weight(wp, wd, n_out, n_in, code, b.PACK_PLAIN)
+    y = torch.full((T, n_out), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(2 * 128 * ((T + 127) // 128) * n_in + 32 * T * n_out + 1024, dtype=torch.uint8, device=DEV)
+    b.trj_linear(to_dev(x, dt), wp, T, n_in, n_out, code, split_k, ws, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), x.astype(np.float64) @ w.astype(np.float64).T
+
+
+@pytest.mark.parametrize("T,n_in,n_out,split_k", [
+    (1, 16, 32, 0), (15, 256, 96, 0), (64, 4096, 512, 1), (64, 4096, 512, 4), (33, 1040, 160, 3),
+    (128, 688, 96, 0), (100, 2048, 256, 2), (200, 512, 64, 0), (64, 11008, 128, 8)])
+def test_bf16_linear(T, n_in, n_out, split_k):
+    got, want = run_linear("bf16", T, n_in, n_out, split_k)
+    assert np.isfinite(got).all()
+    # bf16 inputs are exact on both sides, products are exact in fp32: only the fp32
+    # accumulation order differs
+    assert rel_err(got, want) <= 1e-5
+
+
+@pytest.mark.parametrize("T,n_in,n_out", [(15, 256, 768), (3, 1024, 64), (64, 48, 2048)])
+def test_f32_linear(T, n_in, n_out):
+    got, want = run_linear("f32", T, n_in, n_out, 0)
+    assert rel_err(got, want) <= 1e-5
