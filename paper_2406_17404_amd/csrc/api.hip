@@ -164,7 +164,7 @@ int32_t trj_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in,
 static int kv_convert(void* k_pool, void* v_pool, void* k_plain, void* v_plain, int n_heads,
                       int head_dim, int s_pool, int slot0, int n_slots, int dtype, bool pack,
                       void* stream) {
-  if (!k_pool || !v_pool || !k_plain || !v_plain) return TRJ_ERR_NULLPTR;
+  if (!k_pool || !v_pool || (n_slots > 0 && (!k_plain || !v_plain))) return TRJ_ERR_NULLPTR;
   if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
   if (n_heads < 1 || head_dim < 32 || (head_dim & 31) || s_pool < 32 || (s_pool & 31) ||
       slot0 < 0 || n_slots < 0 || (long)slot0 + n_slots > s_pool)
@@ -190,7 +190,7 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
   if (!parent || !node_off || !depth || !anc || !status_dev) return TRJ_ERR_NULLPTR;
   if (B < 1 || T < 1 || T < B) return TRJ_ERR_BAD_SHAPE;
   if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
-  return launch_tree_prep(parent, node_off, nullptr, nullptr, B, T, 0, depth, anc, status_dev,
+  return launch_tree_prep(parent, node_off, nullptr, nullptr, B, T, 0, 0, depth, anc, status_dev,
                           nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
@@ -214,7 +214,8 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   carve_tree(c, dtype, B, T, n_heads, head_dim, max_seq_slots, &w);
   if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
-  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, w.depth, w.anc,
+  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots, w.depth,
+                           w.anc,
                            w.status, w.row_slot, w.row_pos, w.row_seq, st));
   if (dtype == TRJ_BF16)
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
@@ -270,7 +271,7 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   if (dtype == TRJ_F32)
     return launch_gemm_f32((const float*)x, (const float*)w_packed, T, n_in, n_out, 0, y, st);
   const int tp = padded_rows(T);
-  int sk = split_k > 0 ? split_k : gemm_bf16_split_k(n_out, tp, n_in);
+  int sk = split_k > 0 ? gemm_bf16_clamp_split(tp, n_in, split_k) : gemm_bf16_split_k(n_out, tp, n_in);
   Carver c(workspace);
   uint16_t* xp = c.take<uint16_t>((size_t)tp * n_in);
   float* part = c.take<float>((size_t)sk * T * n_out);
@@ -313,8 +314,8 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
   hipStream_t st = (hipStream_t)stream;
   const float scale = 1.0f / sqrtf((float)dh);
 
-  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, w.t.depth, w.t.anc,
-                           status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq, st));
+  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots,
+                           w.t.depth, w.t.anc, status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq, st));
   TRJ_TRY(launch_rope_table(w.t.row_pos, T, dh, m.rope_theta, w.cs, st));
   TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
 

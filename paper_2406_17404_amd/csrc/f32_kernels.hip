@@ -129,6 +129,7 @@ __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* 
   const int t = blockIdx.x, half = dh >> 1, hd = n_heads * dh, n_out = 3 * hd;
   const float* y = qkv + (size_t)t * n_out;
   const int slot = row_slot[t];
+  if (slot < 0) return;  // row of a malformed sequence
   for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
     int head = idx / half, j = idx % half;
     float2 c = cs[(size_t)t * half + j];
@@ -187,9 +188,10 @@ __global__ __launch_bounds__(64) void tree_attn_f32_kernel(
   const int t = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
   float* o = out + ((size_t)t * n_heads + head) * dh;
   const int s = row_seq[t];
-  const int L = prefix_len[s], i = t - node_off[s], base = kv_off[s];
+  const int L = s < 0 ? 0 : prefix_len[s], i = s < 0 ? 0 : t - node_off[s];
+  const int base = s < 0 ? 0 : kv_off[s];
   const int nk = L + i + 1;  // ancestors have smaller indices than i
-  if (status_dev[s] != 0 || nk > max_slots || L < 0) {
+  if (s < 0 || status_dev[s] != 0 || nk > max_slots) {
     for (int c = lane; c < dh; c += 64) o[c] = 0.f;
     return;
   }

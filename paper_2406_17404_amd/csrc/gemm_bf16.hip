@@ -244,6 +244,17 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
   return check_launch();
 }
 
+// number of grid splits a request for split_k really gets (never an empty split)
+int gemm_bf16_clamp_split(int tp, int n_in, int split_k) {
+  int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
+  int ck = mt == 4 ? 8 : 16;
+  int nchunks = ((n_in >> 4) + ck - 1) / ck;
+  if (split_k < 1) split_k = 1;
+  if (split_k > nchunks) split_k = nchunks;
+  int cps = (nchunks + split_k - 1) / split_k;
+  return (nchunks + cps - 1) / cps;
+}
+
 int gemm_bf16_split_k(int n_out, int tp, int n_in) {
   // enough workgroups for one per compute unit; projections with a fused epilogue
   // never split

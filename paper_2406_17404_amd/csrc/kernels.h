@@ -15,8 +15,8 @@ extern Tunables g_tune;
 
 // tree_kernels.hip
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
-                     const int32_t* prefix_len, int B, int T, int s_pool, int32_t* depth,
-                     uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
+                     const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
+                     int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
                      int32_t* row_seq, hipStream_t st);
 int launch_argmax(const float* logits, int T, int V, int32_t* out, hipStream_t st);
 int launch_accept(const int32_t* argmax, const int32_t* tok, const int32_t* parent,
@@ -54,6 +54,7 @@ int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_la
 
 // gemm_bf16.hip
 int gemm_bf16_split_k(int n_out, int tp, int n_in);
+int gemm_bf16_clamp_split(int tp, int n_in, int split_k);
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
                           int n_out, int split_k, float* y, hipStream_t st);
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,

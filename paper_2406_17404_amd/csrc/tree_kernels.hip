@@ -11,7 +11,8 @@ namespace trj {
 // One workgroup of TRJ_N_MAX threads per sequence.  A tree is well formed when
 // parent[0] == -1 and 0 <= parent[i] < i; then walking parents strictly decreases the
 // index, so every walk ends at the root.  When the KV arrays are given, the sequence's
-// slot range must also lie inside the pool and start on a block boundary.  Rows of a
+// slot range must also lie inside the pool, start on a block boundary and hold at most
+// max_seq_slots slots (the bound the host sized its launches and scratch with).  Rows of a
 // malformed sequence get depth 0, empty bit rows and row_slot -1, which makes every
 // later kernel skip them.
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
@@ -22,7 +23,7 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
 __global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
     const int32_t* __restrict__ parent, const int32_t* __restrict__ node_off,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ prefix_len, int T, int s_pool,
-    int32_t* __restrict__ depth, uint64_t* __restrict__ anc, int32_t* __restrict__ status_dev,
+    int max_seq_slots, int32_t* __restrict__ depth, uint64_t* __restrict__ anc, int32_t* __restrict__ status_dev,
     int32_t* __restrict__ row_slot, int32_t* __restrict__ row_pos, int32_t* __restrict__ row_seq) {
   __shared__ int32_t par[TRJ_N_MAX];
   __shared__ int32_t bad;
@@ -35,7 +36,9 @@ __global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
     int b = range_ok ? 0 : 1;
     if (kv_off && range_ok) {
       int ko = kv_off[s], L = prefix_len[s];
-      if (ko < 0 || (ko & (TRJ_KV_BLOCK - 1)) || L < 0 || (long)ko + L + n > (long)s_pool) b = 1;
+      if (ko < 0 || (ko & (TRJ_KV_BLOCK - 1)) || L < 0 || (long)ko + L + n > (long)s_pool ||
+          (long)L + n > (long)max_seq_slots)
+        b = 1;
     }
     bad = b;
   }
@@ -70,8 +73,8 @@ __global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
 }
 
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
-                     const int32_t* prefix_len, int B, int T, int s_pool, int32_t* depth,
-                     uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
+                     const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
+                     int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
                      int32_t* row_seq, hipStream_t st) {
   // rows that no valid sequence covers must read as "skip"
   int nb = (T + 255) / 256;
@@ -82,8 +85,8 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
     fill_i32_kernel<<<nb, 256, 0, st>>>(row_pos, 0, T);
     fill_i32_kernel<<<nb, 256, 0, st>>>(row_seq, -1, T);
   }
-  tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool, depth,
-                                            anc, status_dev, row_slot, row_pos, row_seq);
+  tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool,
+                                            max_seq_slots, depth, anc, status_dev, row_slot, row_pos, row_seq);
   return check_launch();
 }
 
@@ -218,7 +221,7 @@ __global__ void kv_compact_kernel(E* __restrict__ k_pool, E* __restrict__ v_pool
   const int a = accept_len[s];
   const int L = prefix_len[s];
   if (plane == 0 && threadIdx.x == 0) new_len[s] = a < 0 ? L : L + a + 1;
-  if (a < 0) return;
+  if (a < 0 || L < 0 || kv_off[s] < 0) return;
   const int base = kv_off[s] + L;
   E* kp = k_pool + layer * layer_stride + (size_t)head * s_pool * dh;
   E* vp = v_pool + layer * layer_stride + (size_t)head * s_pool * dh;
