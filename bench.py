@@ -1,0 +1,228 @@
+"""Benchmark of the TR-Jacobi verify step on one MI355X.
+
+A "step" is one tr_verify_step call (tree bookkeeping, embedding, all decoder layers
+with tree attention, LM head, greedy argmax, longest accepted path, KV compaction) over
+one batch of synthetic input of the LLaMA-7B-shaped workload: bf16, 32 layers, d 4096,
+32x128 heads, FFN 11008, vocab 32000, prefix of 1024 tokens, one 64-node tree.  All
+inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1|C3]
+                    [--no-cpu-baseline] [--no-kernel-times]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def build_device_model(shape, seed, torch, b):
+    """Random-init N(0, 0.02) weights generated on the device (synthetic), packed into
+    the library's tiled layout one matrix at a time."""
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    desc = b.make_desc(shape)
+    dw = b.DeviceWeights(desc)
+    dt = torch.bfloat16
+    d, hd, F, V = shape.d_model, shape.n_heads * shape.head_dim, shape.d_ffn, shape.vocab
+
+    def rnd(n_out, n_in):
+        return (torch.randn(n_out, n_in, device="cuda", dtype=torch.float32, generator=gen) * 0.02).to(dt)
+
+    ones = torch.ones(d, device="cuda", dtype=torch.float32)
+    for _ in range(shape.n_layers):
+        dw.add_layer(ones, rnd(3 * hd, d), rnd(d, hd), ones, rnd(2 * F, d), rnd(d, F))
+    dw.set_globals(rnd(V, d), ones, rnd(V, d))
+    dw.finish()
+    torch.cuda.synchronize()
+    return desc, dw
+
+
+def gemm_bytes(T, n_in, n_out, e=2):
+    return n_out * n_in * e + T * (n_in + n_out) * e
+
+
+def attn_bytes(L, N, H, dh, e=2):
+    return 2 * (L + N) * H * dh * e + 2 * N * H * dh * e
+
+
+def cpu_baseline(wl, n_sample_layers=1):
+    """The CPU oracle on a bounded sample of the same workload: n_sample_layers decoder
+    layers at full shape plus the LM head, argmax, accept and compaction; the layer time
+    is scaled to the model's depth."""
+    import numpy as np
+    from oracle import tr_oracle as O
+    from paper_2406_17404_amd import inputs as I
+    from dataclasses import replace
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    shape = wl.shape
+    small = replace(shape, n_layers=n_sample_layers)
+    L, n = wl.prefix_len[0], wl.tree_size
+    w = I.gen_global_weights(small, wl.seed)
+    w["layers"] = [I.gen_layer_weights(small, wl.seed, l) for l in range(n_sample_layers)]
+    tree = I.gen_trees(wl)[0]
+    tok = I.gen_tokens(shape.vocab, n, wl.seed, "tree")
+    kv = []
+    for l in range(n_sample_layers):
+        k, v = I.gen_prefix_kv(small, wl.seed, l, 0, L)
+        K = np.zeros((shape.n_heads, L + n, shape.head_dim))
+        V = np.zeros_like(K)
+        K[:, :L], V[:, :L] = k, v
+        kv.append((K, V))
+    # time layers and head separately so that the layer part can be scaled
+    t0 = time.perf_counter()
+    logits = O.decoder_tree_forward(small, w, kv, tok, tree, L)
+    t1 = time.perf_counter()
+    am = O.greedy_argmax(logits)
+    a, best, path, bonus = O.accept_path(am, tok, tree)
+    O.kv_compact(kv, path, a, L)
+    t2 = time.perf_counter()
+    # LM head share of the forward: one rmsnorm + [n, d] x [d, V]
+    th0 = time.perf_counter()
+    hf = O.rmsnorm(np.zeros((n, shape.d_model)) + 1.0, w["g_final"], shape.rms_eps)
+    _ = hf @ np.asarray(w["w_lm"], np.float64).T
+    th1 = time.perf_counter()
+    t_head = th1 - th0
+    t_layers = max((t1 - t0) - t_head, 1e-9)
+    t_tail = (t2 - t1) * shape.n_layers / n_sample_layers  # compaction scales with layers
+    est = t_layers * shape.n_layers / n_sample_layers + t_head + t_tail
+    return {"value": n / est, "unit": "tree tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_sample_layers} of {shape.n_layers} decoder layers at full shape + LM head, "
+                      f"argmax, accept, compaction; layer time scaled x{shape.n_layers // n_sample_layers}; "
+                      f"measured {t2 - t0:.1f} s, estimated full step {est:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C1", choices=["C1", "C3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-times", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (--gpus 1); the verify step is a "
+              "single-GPU path and no multi-GPU figure exists", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2406_17404_amd import binding as b
+    from paper_2406_17404_amd import inputs as I
+
+    b.lib()  # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "needs a GPU"
+    wl = I.workload(args.workload)
+    shape = wl.shape
+    H, dh, nl = shape.n_heads, shape.head_dim, shape.n_layers
+    L, N = wl.prefix_len[0], wl.tree_size
+    desc, dw = build_device_model(shape, wl.seed, torch, b)
+
+    tree = I.gen_trees(wl)[0]
+    tok_h = I.gen_tokens(shape.vocab, N, wl.seed, "tree")
+    kv_off_h, s_pool = I.pool_offsets([L], [N])
+    dev = "cuda"
+    i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(dev)
+    parent, tok = i32(tree), i32(tok_h)
+    node_off, kv_off, prefix = i32([0, N]), i32(kv_off_h), i32([L])
+    stride = H * s_pool * dh
+    # prefix K/V ~ N(0,1) (synthetic, written straight into the tiled pool)
+    gen = torch.Generator(device=dev).manual_seed(wl.seed + 1)
+    k_pool = torch.randn(nl, stride, device=dev, dtype=torch.float32, generator=gen).to(torch.bfloat16)
+    v_pool = torch.randn(nl, stride, device=dev, dtype=torch.float32, generator=gen).to(torch.bfloat16)
+    ws = torch.empty(b.trj_workspace_bytes(desc, N, 1, L + N), dtype=torch.uint8, device=dev)
+    logits = torch.empty(N, shape.vocab, dtype=torch.float32, device=dev)
+    outs = {k: torch.zeros(n, dtype=torch.int32, device=dev)
+            for k, n in dict(argmax=N, accept_len=1, best=1, bonus=1, new_len=1, status=1).items()}
+    path = torch.zeros(1, b.N_MAX, dtype=torch.int32, device=dev)
+
+    def step():
+        b.tr_verify_step(desc, dw.struct, k_pool, v_pool, stride, s_pool, tok, parent, node_off,
+                         kv_off, prefix, 1, N, L + N, ws, logits, outs["argmax"], outs["accept_len"],
+                         outs["best"], path, outs["bonus"], outs["new_len"], outs["status"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    assert int(outs["status"].cpu()[0]) == 0 and bool(torch.isfinite(logits).all())
+
+    # per-kernel launch durations, HIP events on the launch stream, same steps again
+    kernels = {}
+    if not args.no_kernel_times:
+        d, hd, F, V = shape.d_model, H * dh, shape.d_ffn, shape.vocab
+        alg = {"gemm_qkv": gemm_bytes(N, d, 3 * hd), "tree_attn": attn_bytes(L, N, H, dh),
+               "gemm_o": gemm_bytes(N, hd, d), "gemm_gate_up": gemm_bytes(N, d, 2 * F) - N * F * 2,
+               "gemm_down": gemm_bytes(N, F, d), "gemm_lm": N * d * 2 + V * d * 2 + N * V * 4,
+               "attn_combine": 0, "reduce_norm": 0}
+        flops = {"gemm_qkv": 2 * N * d * 3 * hd, "gemm_o": 2 * N * hd * d, "gemm_gate_up": 2 * N * d * 2 * F,
+                 "gemm_down": 2 * N * F * d, "gemm_lm": 2 * N * d * V, "tree_attn": 4 * N * (L + N) * H * dh}
+        for name in ("gemm_gate_up", "gemm_qkv", "gemm_down", "gemm_o", "gemm_lm", "tree_attn",
+                     "attn_combine", "reduce_norm"):
+            cap = args.steps * (2 * nl + 2)
+            b.trj_profile_begin(b.KERNEL_CLASSES[name], cap)
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            times = b.trj_profile_end(cap)
+            avg_ms = sum(times) / max(len(times), 1)
+            k = {"launches_per_step": len(times) // args.steps, "avg_us": round(avg_ms * 1e3, 2)}
+            if alg.get(name):
+                k["alg_bytes"] = alg[name]
+                k["GBps"] = round(alg[name] / (avg_ms * 1e-3) / 1e9, 1)
+                k["frac_hbm"] = round(k["GBps"] / HBM_PEAK_GBS, 4)
+            if name in flops:
+                k["TFLOPs"] = round(flops[name] / (avg_ms * 1e-3) / 1e12, 2)
+                k["frac_mfma"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
+            kernels[name] = k
+
+    roof = None
+    if kernels:
+        dom = max((k for k in kernels if kernels[k].get("alg_bytes")),
+                  key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])
+        kd = kernels[dom]
+        roof = {"kernel": dom, "bound": "hbm", "achieved": kd["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(kd["GBps"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_us": kd["avg_us"], "alg_bytes_per_launch": kd["alg_bytes"]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl)
+
+    out = {
+        "metric": "verified tree tokens/s (7B-shape verify step) + tree-attn HBM GB/s, % peak",
+        "value": round(N / (ms * 1e-3), 1), "unit": "tree tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: LLaMA-7B-shaped decoder bf16, 32 layers, d 4096, 32x128 heads, "
+                               f"FFN 11008, vocab {shape.vocab}, prefix {L}, {N}-node tree, batch 1",
+                   "tree_rows": N, "prefix_len": L},
+        "tree_attn": kernels.get("tree_attn"),
+        "step_hbm_lower_bound_ms": round((sum(p.numel() for p in dw._keep if p.dtype == torch.bfloat16) * 2
+                                          - shape.vocab * shape.d_model * 2
+                                          + nl * attn_bytes(L, N, H, dh)) / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
+        "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -143,6 +143,17 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
  * summation order. */
 int32_t trj_set_tunable(const char* name, int32_t value);
 
+/* Per-kernel timing for benchmarks.  Between trj_profile_begin(kernel_class, capacity)
+ * and trj_profile_end, every launch of that kernel class inside the entry points is
+ * bracketed by HIP events on its stream (the only HIP objects this library ever
+ * creates).  trj_profile_end waits for them, writes up to `capacity` durations in
+ * milliseconds to h_ms, their number to h_count, and destroys the events.  Classes:
+ * 1 QKV projection, 2 tree attention, 3 attention merge, 4 output projection, 5 split-k
+ * sum + residual + RMSNorm, 6 gate/up projection, 7 down projection, 8 LM head, 9 argmax,
+ * 10 accept, 11 KV compaction. */
+int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity);
+int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count);
+
 /* Tree bookkeeping: depth[i] = depth[parent[i]] + 1 (root 0) and the ancestor-or-self
  * bit rows of the sparse tree mask (appendix "Templates for Token Tree"): bit j%64 of
  * anc[i][j/64] is set when node j is on the path root..i.  A sequence whose tree is

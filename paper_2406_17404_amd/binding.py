@@ -53,6 +53,8 @@ _SIGS = {
     "trj_version": (C.c_char_p, []),
     "trj_last_hip_error": (_i32, []),
     "trj_set_tunable": (_i32, [C.c_char_p, _i32]),
+    "trj_profile_begin": (_i32, [_i32, _i32]),
+    "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
     "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
     "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "trj_kv_pack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -119,6 +121,22 @@ def trj_version() -> str:
 
 def trj_set_tunable(name: str, value: int) -> None:
     _check("trj_set_tunable", lib().trj_set_tunable(name.encode(), int(value)))
+
+
+KERNEL_CLASSES = {"gemm_qkv": 1, "tree_attn": 2, "attn_combine": 3, "gemm_o": 4, "reduce_norm": 5,
+                  "gemm_gate_up": 6, "gemm_down": 7, "gemm_lm": 8, "argmax": 9, "accept": 10,
+                  "kv_compact": 11}
+
+
+def trj_profile_begin(kernel_class: int, capacity: int) -> None:
+    _check("trj_profile_begin", lib().trj_profile_begin(kernel_class, capacity))
+
+
+def trj_profile_end(capacity: int) -> List[float]:
+    buf = (C.c_float * capacity)()
+    n = _i32(0)
+    _check("trj_profile_end", lib().trj_profile_end(buf, capacity, C.byref(n)))
+    return [float(buf[i]) for i in range(n.value)]
 
 
 def trj_workspace_bytes(desc: ModelDesc, t_max: int, b_max: int, l_max: int) -> int:

@@ -2,6 +2,7 @@
 // in which the kernels of the verify step are enqueued.  No arithmetic lives here.
 #include <atomic>
 #include <cstring>
+#include <vector>
 
 #include "common.h"
 #include "kernels.h"
@@ -11,6 +12,25 @@ namespace trj {
 Tunables g_tune;
 static std::atomic<int> g_last_hip_error{0};
 void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+
+// ---- optional per-kernel timing (trj_profile_begin / trj_profile_end)
+struct Profiler {
+  int cls = KC_NONE;
+  std::vector<hipEvent_t> start, stop;
+  int used = 0;
+  bool open = false;
+};
+static Profiler g_prof;
+void prof_begin(int cls, hipStream_t st) {
+  if (cls != g_prof.cls || g_prof.used >= (int)g_prof.start.size()) return;
+  (void)hipEventRecord(g_prof.start[g_prof.used], st);
+  g_prof.open = true;
+}
+void prof_end(int cls, hipStream_t st) {
+  if (cls != g_prof.cls || !g_prof.open) return;
+  (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
+  g_prof.open = false;
+}
 
 // bump allocator over the caller's workspace; with base == nullptr it only measures
 struct Carver {
@@ -126,10 +146,53 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
   if (!name) return TRJ_ERR_NULLPTR;
   if (!strcmp(name, "gemm_target_wgs")) g_tune.gemm_target_wgs = value;
   else if (!strcmp(name, "max_split_k")) g_tune.max_split_k = value;
+  else if (!strcmp(name, "gemm_cfg")) g_tune.gemm_cfg = value;
   else if (!strcmp(name, "attn_target_waves")) g_tune.attn_target_waves = value;
   else if (!strcmp(name, "attn_min_bpw")) g_tune.attn_min_bpw = value;
   else return TRJ_ERR_BAD_SHAPE;
   return TRJ_OK;
+}
+
+// Per-kernel timing: between trj_profile_begin and trj_profile_end every launch of the
+// chosen kernel class is bracketed by HIP events on its stream (this is the one place
+// where the library creates HIP objects: the events).  trj_profile_end waits for them and
+// returns the durations in milliseconds.
+int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity) {
+  if (g_prof.cls != KC_NONE || kernel_class <= KC_NONE || kernel_class > KC_SETUP || capacity < 1)
+    return TRJ_ERR_BAD_SHAPE;
+  g_prof.start.resize(capacity);
+  g_prof.stop.resize(capacity);
+  for (int i = 0; i < capacity; ++i) {
+    hipError_t e1 = hipEventCreate(&g_prof.start[i]), e2 = hipEventCreate(&g_prof.stop[i]);
+    if (e1 != hipSuccess || e2 != hipSuccess) {
+      note_hip_error(e1 != hipSuccess ? e1 : e2);
+      return TRJ_ERR_HIP;
+    }
+  }
+  g_prof.used = 0;
+  g_prof.open = false;
+  g_prof.cls = kernel_class;
+  return TRJ_OK;
+}
+int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count) {
+  if (!h_ms || !h_count) return TRJ_ERR_NULLPTR;
+  int rc = TRJ_OK;
+  int n = g_prof.used < capacity ? g_prof.used : capacity;
+  for (int i = 0; i < n; ++i) {
+    hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&h_ms[i], g_prof.start[i], g_prof.stop[i]);
+    if (e != hipSuccess) { note_hip_error(e); rc = TRJ_ERR_HIP; }
+  }
+  *h_count = n;
+  for (size_t i = 0; i < g_prof.start.size(); ++i) {
+    (void)hipEventDestroy(g_prof.start[i]);
+    (void)hipEventDestroy(g_prof.stop[i]);
+  }
+  g_prof.start.clear();
+  g_prof.stop.clear();
+  g_prof.used = 0;
+  g_prof.cls = KC_NONE;
+  return rc;
 }
 
 int32_t trj_workspace_bytes(const trj_model_desc* desc, int32_t t_max, int32_t b_max,
@@ -322,25 +385,25 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
-    TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
-                               w.hp, st));
+    { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
+                               w.hp, st)); }
     for (int l = 0; l < m.n_layers; ++l) {
       const trj_layer_weights& lw = weights->h_layers[l];
       uint16_t* kl = (uint16_t*)k_pool + (size_t)l * kv_layer_stride;
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
-      TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
-                              w.t.row_slot, w.q, kl, vl, st));
+      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
+                              w.t.row_slot, w.q, kl, vl, st)); }
       TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off,
                                     prefix_len, status_dev, B, T, H, dh, s_pool, max_seq_slots,
                                     scale, w.t.attn, 1, tp, w.op, st));
-      TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st));
-      TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st));
-      TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st));
-      TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, w.partial, st));
+      { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }
+      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st)); }
+      { ProfScope ps_(KC_GEMM_GATE_UP, st); TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st)); }
+      { ProfScope ps_(KC_GEMM_DOWN, st); TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, w.partial, st)); }
       const float* g_next = l + 1 < m.n_layers ? weights->h_layers[l + 1].g_attn : weights->g_final;
-      TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st));
+      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st)); }
     }
-    TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st));
+    { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st)); }
   } else {
     for (int l = 0; l < m.n_layers; ++l) {
       const trj_layer_weights& lw = weights->h_layers[l];
@@ -360,9 +423,10 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
     TRJ_TRY(launch_rmsnorm_f32(w.x, weights->g_final, T, d, m.rms_eps, w.h, st));
     TRJ_TRY(launch_gemm_f32(w.h, (const float*)weights->w_lm, T, d, V, 0, lg, st));
   }
-  TRJ_TRY(launch_argmax(lg, T, V, argmax_out, st));
-  TRJ_TRY(launch_accept(argmax_out, tok, parent, node_off, status_dev, B, T, accept_len, best_node,
-                        path, bonus_tok, status_dev, st));
+  { ProfScope ps_(KC_ARGMAX, st); TRJ_TRY(launch_argmax(lg, T, V, argmax_out, st)); }
+  { ProfScope ps_(KC_ACCEPT, st); TRJ_TRY(launch_accept(argmax_out, tok, parent, node_off, status_dev, B, T, accept_len, best_node,
+                        path, bonus_tok, status_dev, st)); }
+  ProfScope ps_(KC_KV_COMPACT, st);
   return launch_kv_compact(k_pool, v_pool, kv_layer_stride, path, accept_len, kv_off, prefix_len, B,
                            m.n_layers, H, dh, s_pool, m.dtype, new_len, st);
 }

@@ -281,13 +281,16 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   int waves = nsplit_max * qg_max;
   dim3 grid((waves + 3) / 4, n_heads, B);
 #define TRJ_ATTN(D, Q) tree_attn_bf16_kernel<D, Q><<<grid, 256, 0, st>>>(a)
+  prof_begin(KC_ATTN, st);
   if (dh == 128) { if (nqt == 1) TRJ_ATTN(128, 1); else TRJ_ATTN(128, 2); }
   else { if (nqt == 1) TRJ_ATTN(64, 1); else TRJ_ATTN(64, 2); }
 #undef TRJ_ATTN
+  prof_end(KC_ATTN, st);
   int rc = check_launch();
   if (rc) return rc;
   int rows_out = tiled ? tp : T;
   dim3 cgrid(rows_out, (n_heads * dh / 8 + 255) / 256);
+  ProfScope ps_(KC_ATTN_COMBINE, st);
   if (dh == 128)
     attn_combine_kernel<128><<<cgrid, 256, 0, st>>>(po, pm, pl, row_seq, node_off, prefix_len,
                                                     status_dev, T, n_heads, bpw, nsplit_max, tiled,

@@ -75,6 +75,14 @@ __host__ __device__ inline int logical_row(int r, int kind, int n_out, int n_hea
   return r;
 }
 
+// Workgroup barrier that orders LDS traffic only: each wavefront waits for its own LDS
+// operations and then joins the barrier, while its outstanding global loads stay in
+// flight (the generic barrier would first drain them, which empties a register prefetch
+// ring at every k-chunk).
+__device__ inline void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // ---- error bookkeeping (defined in api.hip)
 void note_hip_error(hipError_t e);
 inline int check_launch() {

@@ -3,16 +3,20 @@
 // With T of 64..128 the product is bound by streaming W once from HBM, so the kernel is
 // organised around that stream: W is stored in 32x16 tiles that are exactly one
 // v_mfma_f32_32x32x16_bf16 A operand (each lane's 16 bytes, 1 KiB per wavefront load,
-// fully coalesced, straight from HBM into registers, no LDS).  The activations (a few
-// hundred KiB, L2 resident) are the B operand: they are kept in the same tiled form in
-// global memory, staged through LDS once per workgroup and k-chunk, and shared by the
-// workgroup's wavefronts.
+// fully coalesced, straight from HBM into a ring of registers, no LDS).  The activations
+// (a few hundred KiB, L2 resident) are the B operand: they are kept in the same tiled form
+// in global memory, staged through LDS in phases and shared by the workgroup's wavefronts.
+// The epilogue functors fuse what follows the projection: rotary + KV-cache write (QKV),
+// SiLU(g)*u (gate/up), plain fp32 stores (split-k partial sums, logits).
 //
-// Workgroup = 4 wavefronts = 2 row tiles (64 output features) x 2 halves of every
-// k-chunk; the two k-halves are added through LDS at the end.  grid = (n_out/64,
-// split_k, token blocks).  The epilogue functors fuse what follows the projection:
-// rotary + KV-cache write (QKV), SiLU(g)*u (gate/up), plain fp32 stores (split-k
-// partial sums, logits).
+// What the measurements on gfx950 dictated (each of these cost 20-40 % when violated):
+//  - every global load in the main loop is unconditional (indices clamped, never
+//    predicated) and wave-uniform values are made visibly uniform (readfirstlane);
+//    otherwise the compiler cannot count the loads in flight and waits for all of them;
+//  - the barrier between phases orders LDS traffic only, it does not drain global loads;
+//  - the activation loads of a phase are issued at the start of the previous phase, so
+//    they are older than every W load issued since and waiting for them costs nothing;
+//  - a scheduling barrier keeps each W reload next to the step that freed its register.
 #include "common.h"
 #include "kernels.h"
 
@@ -22,7 +26,7 @@ struct GemmArgs {
   const uint16_t* xp;  // activations, tiled (a_off), tp rows
   const uint16_t* w;   // weights, tiled (w_off)
   int n_in, n_out, tp;
-  int chunks_per_split;
+  int chunks_per_split;  // phases per k-split
 };
 
 // acc layout of v_mfma_f32_32x32x16: lane l, register v -> tile row 8*(v/4) + 4*(l/32) +
@@ -119,28 +123,36 @@ struct EpiQKV {
   }
 };
 
-template <int MT, class Epi>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, Epi epi) {
-  constexpr int CK = MT == 4 ? 8 : 16;  // k-steps (of 16) per chunk
-  constexpr int WS = CK / 2;            // k-steps per wavefront and chunk
-  constexpr int XL = MT * CK * 64 / 256;  // 16-byte granules of X per thread and chunk
-  constexpr int BUF = MT * CK * 64;     // granules per LDS buffer
+// Main loop.  Workgroup = RT row tiles x KW k-parts wavefronts, no loader.
+// The k-range is walked in phases of PH k-steps; the activations of a phase (PH*MT KiB)
+// sit in one of two LDS buffers.  Every wavefront
+//   - streams its W tiles through a ring of PF registers that runs across phases, and
+//   - at the START of a phase issues its share of the loads for the phase after next
+//     (kept in registers), and at the END of the phase stores the previous share to the
+//     other LDS buffer, followed by one LDS-only barrier.
+// Because the activation loads are older than every W load issued during the phase,
+// waiting for them at the phase end never stalls the W ring.
+template <int MT, int RT, int KW, int PH, int PF, class Epi>
+__global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi epi) {
+  constexpr int NWV = RT * KW;
+  constexpr int WS = PH / KW;             // k-steps per wavefront and phase
+  constexpr int XG = PH * MT * 64;        // 16-byte granules per phase buffer
+  constexpr int XL = XG / (NWV * 64);     // activation loads per lane and phase
+  static_assert(PH % KW == 0 && WS % PF == 0 && XG % (NWV * 64) == 0, "phase shape");
   extern __shared__ __align__(16) uint8_t smem[];
   u32x4* lds = reinterpret_cast<u32x4*>(smem);
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int rh = wv & 1, kh = wv >> 1;
-  const int ntiles = a.n_out >> 5;
-  const int tile = blockIdx.x * 2 + rh;
-  const bool tile_ok = tile < ntiles;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and the compiler knows
+  const int rt = wv % RT, kw = wv / RT;
   const int ksteps = a.n_in >> 4;
-  const int nchunks = (ksteps + CK - 1) / CK;
-  const int c0 = blockIdx.y * a.chunks_per_split;
-  const int c1 = min(nchunks, c0 + a.chunks_per_split);
+  const int nph = (ksteps + PH - 1) / PH;
+  const int ph0 = blockIdx.y * a.chunks_per_split;
+  const int ph1 = min(nph, ph0 + a.chunks_per_split);
   const int tb = blockIdx.z, ttiles = a.tp >> 5;
-  const u32x4* wp =
-      reinterpret_cast<const u32x4*>(a.w) + (size_t)(tile_ok ? tile : 0) * ksteps * 64 + lane;
-  const u32x4* xg = reinterpret_cast<const u32x4*>(a.xp);
+  const int ntiles = a.n_out >> 5;
+  const int tile = blockIdx.x * RT + rt;
+  const bool tile_ok = tile < ntiles;
   const u32x4 zero = {0, 0, 0, 0};
 
   f32x16 acc[MT];
@@ -149,126 +161,174 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, Epi epi) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
 
-  u32x4 w0[WS], w1[WS], xr[XL];
-
-  auto load_w = [&](int c, u32x4* dst) {
+  if (ph0 < ph1) {
+    const int n = (ph1 - ph0) * WS;  // k-steps of this wavefront
+    const u32x4* wp =
+        reinterpret_cast<const u32x4*>(a.w) + (size_t)(tile_ok ? tile : 0) * ksteps * 64 + lane;
+    const u32x4* xg = reinterpret_cast<const u32x4*>(a.xp) + (size_t)tb * MT * 64;
+    // all indices are clamped, never predicated
+    auto w_load = [&](int i) -> u32x4 {
+      i = min(i, n - 1);
+      int ph = i / WS, s = i - ph * WS;
+      int ks = min((ph0 + ph) * PH + kw * WS + s, ksteps - 1);  // X is zero beyond n_in
+      return wp[(size_t)ks * 64];
+    };
+    u32x4 xa[XL];
+    auto x_load = [&](int ph) {
+      ph = min(ph, ph1 - 1);
 #pragma unroll
-    for (int s = 0; s < WS; ++s) {
-      int ks = c * CK + kh * WS + s;
-      dst[s] = ks < ksteps ? wp[(size_t)ks * 64] : zero;
-    }
-  };
-  auto load_x = [&](int c) {
-#pragma unroll
-    for (int it = 0; it < XL; ++it) {
-      int g = it * 256 + tid;
-      int ksl = g / (MT * 64), rem = g % (MT * 64);
-      int ks = c * CK + ksl;
-      xr[it] = ks < ksteps ? xg[((size_t)ks * ttiles + tb * MT) * 64 + rem] : zero;
-    }
-  };
-  auto store_x = [&](int buf) {
-#pragma unroll
-    for (int it = 0; it < XL; ++it) lds[buf * BUF + it * 256 + tid] = xr[it];
-  };
-  auto compute = [&](int buf, const u32x4* wr) {
-#pragma unroll
-    for (int s = 0; s < WS; ++s) {
-      int ksl = kh * WS + s;
-      bf16x8 wa = __builtin_bit_cast(bf16x8, wr[s]);
-#pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        bf16x8 xb = __builtin_bit_cast(bf16x8, lds[buf * BUF + (ksl * MT + m) * 64 + lane]);
-        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[m], 0, 0, 0);
+      for (int j = 0; j < XL; ++j) {
+        int g = j * (NWV * 64) + tid;
+        int ksl = g / (MT * 64), rem = g - ksl * (MT * 64);
+        int ks = ph * PH + ksl;
+        xa[j] = xg[(size_t)min(ks, ksteps - 1) * ttiles * 64 + rem];
       }
-    }
-  };
-
-  if (c0 < c1) {
-    load_w(c0, w0);
-    load_x(c0);
-    store_x(0);
-    __syncthreads();
-    for (int c = c0; c < c1; c += 2) {
-      // even step: compute buffer 0 / w0, prefetch into buffer 1 / w1
-      bool more = c + 1 < c1;
-      if (more) { load_w(c + 1, w1); load_x(c + 1); }
-      compute(0, w0);
-      if (more) store_x(1);
-      __syncthreads();
-      if (!more) break;
-      // odd step
-      bool more2 = c + 2 < c1;
-      if (more2) { load_w(c + 2, w0); load_x(c + 2); }
-      compute(1, w1);
-      if (more2) store_x(0);
-      __syncthreads();
+    };
+    // k beyond n_in must contribute nothing: zeroed here, at store time, because a select
+    // right after the load would make the wavefront wait for it (and for the whole ring)
+    auto x_store = [&](int buf, int ph) {
+#pragma unroll
+      for (int j = 0; j < XL; ++j) {
+        int g = j * (NWV * 64) + tid;
+        int ks = ph * PH + g / (MT * 64);
+        lds[buf * XG + g] = ks < ksteps ? xa[j] : zero;
+      }
+    };
+    u32x4 wr[PF];
+    x_load(ph0);
+#pragma unroll
+    for (int p = 0; p < PF; ++p) wr[p] = w_load(p);
+    x_store(0, ph0);
+    x_load(ph0 + 1);
+    lds_barrier();
+    int i = 0;
+    for (int ph = ph0; ph < ph1; ++ph) {
+      const int buf = (ph - ph0) & 1;
+#pragma unroll
+      for (int r = 0; r < WS / PF; ++r) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+          bf16x8 wa = __builtin_bit_cast(bf16x8, wr[p]);
+#pragma unroll
+          for (int m = 0; m < MT; ++m) {
+            bf16x8 xb = __builtin_bit_cast(
+                bf16x8, lds[buf * XG + ((kw * WS + r * PF + p) * MT + m) * 64 + lane]);
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[m], 0, 0, 0);
+          }
+          wr[p] = w_load(i + r * PF + p + PF);
+          __builtin_amdgcn_sched_barrier(0);  // keep each reload next to its step
+        }
+      }
+      i += WS;
+      x_store(buf ^ 1, ph + 1);  // activations of the next phase (unused after the last one)
+      lds_barrier();
+      x_load(ph + 2);
     }
   }
 
-  // add the two k-halves through LDS (the chunk buffers are free after the last barrier)
-  float* red = reinterpret_cast<float*>(smem);
-  if (kh == 1) {
+  if (KW > 1) {
+    // add the KW partial sums of a row tile through LDS (all phase reads are behind the
+    // last barrier)
+    float* red = reinterpret_cast<float*>(smem);
+    if (ph0 >= ph1) lds_barrier();
+    if (kw > 0) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+      for (int m = 0; m < MT; ++m)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) red[((rh * MT + m) * 16 + v) * 64 + lane] = acc[m][v];
-  }
-  __syncthreads();
-  if (kh == 0 && tile_ok) {
+        for (int v = 0; v < 16; ++v)
+          red[((((kw - 1) * RT + rt) * MT + m) * 16 + v) * 64 + lane] = acc[m][v];
+    }
+    lds_barrier();
+    if (kw == 0) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
+      for (int q = 1; q < KW; ++q)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[m][v] += red[((rh * MT + m) * 16 + v) * 64 + lane];
-      epi(acc[m], tile, tb * MT + m, lane, blockIdx.y);
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[m][v] += red[((((q - 1) * RT + rt) * MT + m) * 16 + v) * 64 + lane];
     }
   }
+  if (kw == 0 && tile_ok) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m) epi(acc[m], tile, tb * MT + m, lane, blockIdx.y);
+  }
+}
+
+template <int MT, int RT, int KW, class Epi>
+static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
+                     int split_k, const Epi& epi, hipStream_t st) {
+  constexpr int PH = MT == 4 ? 16 : 32;
+  constexpr int WS = PH / KW;
+  constexpr int PF = WS < 16 ? WS : 16;
+  int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
+  if (split_k < 1) split_k = 1;
+  if (split_k > nph) split_k = nph;
+  int pps = (nph + split_k - 1) / split_k;
+  split_k = (nph + pps - 1) / pps;
+  GemmArgs a{xp, w, n_in, n_out, tp, pps};
+  dim3 grid((n_out / 32 + RT - 1) / RT, split_k, tp / (32 * MT));
+  size_t lds_x = (size_t)2 * PH * MT * 1024, lds_r = (size_t)(KW - 1) * RT * MT * 4096;
+  size_t lds = lds_x > lds_r ? lds_x : lds_r;
+  auto kern = gemm_p_kernel<MT, RT, KW, PH, PF, Epi>;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  kern<<<grid, RT * KW * 64, lds, st>>>(a, epi);
+}
+
+// (RT, KW) per shape: enough workgroups to cover the chip and enough wavefronts in flight
+// (about 700 x 16 KiB saturate HBM here), with as many rows per workgroup as that allows,
+// because a workgroup re-reads the whole activation slice for its rows.
+struct GemmPlan {
+  int mt, rt, kw, ph, split_k;
+};
+static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
+  GemmPlan g;
+  g.mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
+  g.ph = g.mt == 4 ? 16 : 32;
+  int nph = ((n_in >> 4) + g.ph - 1) / g.ph;
+  if (split_k < 1) split_k = 1;
+  if (split_k > nph) split_k = nph;
+  int pps = (nph + split_k - 1) / split_k;
+  g.split_k = (nph + pps - 1) / pps;  // never an empty split
+  int ntiles = n_out >> 5, tblocks = tp / (32 * g.mt);
+  int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2)
+  if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt == 4 ? 3 : 2);
+  g.rt = shape == 1 ? 4 : 2;
+  g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : 2);
+  return g;
 }
 
 template <class Epi>
 static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
                        int split_k, const Epi& epi, hipStream_t st) {
-  int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
-  if (tp % (32 * mt) != 0 || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
-  int ck = mt == 4 ? 8 : 16;
-  int ksteps = n_in >> 4, nchunks = (ksteps + ck - 1) / ck;
-  if (split_k < 1) split_k = 1;
-  if (split_k > nchunks) split_k = nchunks;
-  int cps = (nchunks + split_k - 1) / split_k;
-  GemmArgs a{xp, w, n_in, n_out, tp, cps};
-  dim3 grid((n_out / 32 + 1) / 2, split_k, tp / (32 * mt));
-  size_t lds = (size_t)2 * mt * ck * 1024;
-  if (mt == 1) gemm_bf16_kernel<1, Epi><<<grid, 256, lds, st>>>(a, epi);
-  else if (mt == 2) gemm_bf16_kernel<2, Epi><<<grid, 256, lds, st>>>(a, epi);
-  else gemm_bf16_kernel<4, Epi><<<grid, 256, lds, st>>>(a, epi);
+  if (tp < 32 || (tp & 31) || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
+  GemmPlan g = plan_gemm(tp, n_in, n_out, split_k);
+  if (tp % (32 * g.mt) != 0) return TRJ_ERR_BAD_SHAPE;
+#define TRJ_P(M)                                                                             \
+  do {                                                                                       \
+    if (g.rt == 4) launch_p<M, 4, 1, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);       \
+    else if (g.kw == 4) launch_p<M, 2, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);  \
+    else launch_p<M, 2, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);                 \
+  } while (0)
+  if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else TRJ_P(4);
+#undef TRJ_P
   return check_launch();
 }
 
-// number of grid splits a request for split_k really gets (never an empty split)
+// number of grid splits a request for split_k really gets
 int gemm_bf16_clamp_split(int tp, int n_in, int split_k) {
-  int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
-  int ck = mt == 4 ? 8 : 16;
-  int nchunks = ((n_in >> 4) + ck - 1) / ck;
-  if (split_k < 1) split_k = 1;
-  if (split_k > nchunks) split_k = nchunks;
-  int cps = (nchunks + split_k - 1) / split_k;
-  return (nchunks + cps - 1) / cps;
+  return plan_gemm(tp, n_in, 32, split_k).split_k;
 }
 
 int gemm_bf16_split_k(int n_out, int tp, int n_in) {
-  // enough workgroups for one per compute unit; projections with a fused epilogue
-  // never split
+  // projections whose epilogue is a plain partial-sum store are split along k until the
+  // launch has about one workgroup (of 2 row tiles) per compute unit
   int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
-  int ck = mt == 4 ? 8 : 16;
   int groups = ((n_out / 32 + 1) / 2) * (tp / (32 * mt));
-  int nchunks = ((n_in >> 4) + ck - 1) / ck;
   int sk = (g_tune.gemm_target_wgs + groups - 1) / groups;
   if (sk > g_tune.max_split_k) sk = g_tune.max_split_k;
-  if (sk > nchunks) sk = nchunks;
-  if (sk < 1) sk = 1;
-  // the number of non-empty splits for the chosen chunks-per-split
-  int cps = (nchunks + sk - 1) / sk;
-  return (nchunks + cps - 1) / cps;
+  return gemm_bf16_clamp_split(tp, n_in, sk);
 }
 
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,

@@ -8,10 +8,27 @@ namespace trj {
 struct Tunables {
   int gemm_target_wgs = 256;   // split-k is raised until a GEMM has this many workgroups
   int max_split_k = 8;
+  int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..3 force one
   int attn_target_waves = 1024;
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
 extern Tunables g_tune;
+
+// per-kernel timing hooks (api.hip): when kernel class `cls` is being profiled, a HIP
+// event is recorded on the stream before and after the launch
+enum KernelClass {
+  KC_NONE = 0, KC_GEMM_QKV = 1, KC_ATTN = 2, KC_ATTN_COMBINE = 3, KC_GEMM_O = 4,
+  KC_REDUCE_NORM = 5, KC_GEMM_GATE_UP = 6, KC_GEMM_DOWN = 7, KC_GEMM_LM = 8, KC_ARGMAX = 9,
+  KC_ACCEPT = 10, KC_KV_COMPACT = 11, KC_SETUP = 12
+};
+void prof_begin(int cls, hipStream_t st);
+void prof_end(int cls, hipStream_t st);
+struct ProfScope {
+  int cls;
+  hipStream_t st;
+  ProfScope(int c, hipStream_t s) : cls(c), st(s) { prof_begin(cls, st); }
+  ~ProfScope() { prof_end(cls, st); }
+};
 
 // tree_kernels.hip
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,

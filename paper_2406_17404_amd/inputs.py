@@ -98,14 +98,28 @@ def bf16_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def bf16_round(x: np.ndarray) -> np.ndarray:
-    return bf16_to_f32(bf16_bits(x))
+    """fp32 values rounded to the nearest bf16 (ties to even), returned as fp32."""
+    u = np.array(x, dtype=np.float32, copy=True).view(np.uint32)
+    t = u >> 16
+    t &= 1
+    t += 0x7FFF
+    u += t
+    u &= np.uint32(0xFFFF0000)
+    return u.view(np.float32)
 
 
 def _normal(rng, shape, std, dtype):
     x = rng.standard_normal(shape, dtype=np.float32)
     if std != 1.0:
         x *= np.float32(std)
-    return bf16_round(x) if dtype == "bf16" else x
+    if dtype == "bf16":  # round in place: these arrays can be hundreds of MB
+        u = x.view(np.uint32)
+        t = u >> 16
+        t &= 1
+        t += 0x7FFF
+        u += t
+        u &= np.uint32(0xFFFF0000)
+    return x
 
 
 # ----------------------------------------------------------------------------- weights
