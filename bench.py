@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--workload", default="C1", choices=["C1", "C3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-times", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="launch-shape knob for experiments (see trj_set_tunable)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (--gpus 1); the verify step is a "
@@ -123,6 +125,9 @@ def main():
     from paper_2406_17404_amd import inputs as I
 
     b.lib()  # fail loudly if the HIP library is not built
+    for kv in args.tune:
+        name, value = kv.split("=")
+        b.trj_set_tunable(name, int(value))
     assert torch.cuda.is_available(), "needs a GPU"
     wl = I.workload(args.workload)
     shape = wl.shape

@@ -139,7 +139,7 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
                    void* stream);
 
 /* Launch-shape knobs for experiments: "gemm_target_wgs", "max_split_k",
- * "attn_target_waves", "attn_min_bpw".  Results do not depend on them beyond fp32
+ * "gemm_cfg", "attn_target_wgs", "attn_min_bpw".  Results do not depend on them beyond fp32
  * summation order. */
 int32_t trj_set_tunable(const char* name, int32_t value);
 

@@ -72,8 +72,8 @@ static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int ma
   w->anc = c.take<uint64_t>(2 * (size_t)T);
   w->attn = nullptr;
   if (dtype == TRJ_BF16) {
-    int nqt, qg, bpw, ns;
-    attn_bf16_plan(B, T, H, max_seq_slots, &nqt, &qg, &bpw, &ns);
+    int ntw, qg, bpwg, ns;
+    attn_bf16_plan(B, T, H, max_seq_slots, &ntw, &qg, &bpwg, &ns);
     w->attn = c.take<float>(attn_bf16_ws_floats(T, H, dh, ns));
   }
 }
@@ -147,7 +147,7 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
   if (!strcmp(name, "gemm_target_wgs")) g_tune.gemm_target_wgs = value;
   else if (!strcmp(name, "max_split_k")) g_tune.max_split_k = value;
   else if (!strcmp(name, "gemm_cfg")) g_tune.gemm_cfg = value;
-  else if (!strcmp(name, "attn_target_waves")) g_tune.attn_target_waves = value;
+  else if (!strcmp(name, "attn_target_wgs")) g_tune.attn_target_wgs = value;
   else if (!strcmp(name, "attn_min_bpw")) g_tune.attn_min_bpw = value;
   else return TRJ_ERR_BAD_SHAPE;
   return TRJ_OK;
@@ -280,11 +280,14 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots, w.depth,
                            w.anc,
                            w.status, w.row_slot, w.row_pos, w.row_seq, st));
-  if (dtype == TRJ_BF16)
+  if (dtype == TRJ_BF16) {
+    // rows of malformed sequences read as zeros
+    TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
-                                 (const uint16_t*)v_layer, w.anc, w.row_seq, node_off, kv_off,
-                                 prefix_len, w.status, B, T, n_heads, head_dim, s_pool,
-                                 max_seq_slots, scale, w.attn, 0, 0, (uint16_t*)out, st);
+                                 (const uint16_t*)v_layer, w.anc, w.row_seq, node_off, kv_off, prefix_len,
+                                 w.status, B, T, n_heads, head_dim, s_pool, max_seq_slots, scale,
+                                 w.attn, 0, 0, (uint16_t*)out, st);
+  }
   return launch_tree_attn_f32((const float*)q, (const float*)k_layer, (const float*)v_layer, w.anc,
                               w.row_seq, node_off, kv_off, prefix_len, w.status, T, n_heads,
                               head_dim, s_pool, max_seq_slots, scale, (float*)out, st);
@@ -385,6 +388,8 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
+    // attention output: padding rows and rows of malformed sequences stay zero all step
+    TRJ_TRY(launch_zero_bytes(w.op, (size_t)tp * hd * 2, st));
     { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
                                w.hp, st)); }
     for (int l = 0; l < m.n_layers; ++l) {
@@ -393,9 +398,9 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
       { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
                               w.t.row_slot, w.q, kl, vl, st)); }
-      TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off,
-                                    prefix_len, status_dev, B, T, H, dh, s_pool, max_seq_slots,
-                                    scale, w.t.attn, 1, tp, w.op, st));
+      TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off, prefix_len, status_dev,
+                                    B, T, H, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
+                                    w.op, st));
       { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }
       { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st)); }
       { ProfScope ps_(KC_GEMM_GATE_UP, st); TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st)); }

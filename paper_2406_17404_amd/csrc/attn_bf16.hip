@@ -1,9 +1,10 @@
 // Tree-masked attention, bf16 storage, fp32 softmax and accumulation.
 //
-// The work is streaming the sequence's K/V once; every wavefront owns a contiguous
-// range of 32-slot blocks of one (sequence, head) and up to 64 query rows (tree nodes).
-// K and V blocks are tiled in memory so that each lane's 16-byte load is directly an
-// MFMA A operand (1 KiB coalesced per wavefront load, no LDS):
+// The work is streaming the sequence's K/V once.  A workgroup of 8 wavefronts owns a
+// contiguous range of 32-slot blocks of one (sequence, head) and one group of 32 or 64
+// query rows (tree nodes); wavefront (kstream, qtile) walks every KS-th block of the range
+// for one tile of 32 queries.  K and V blocks are tiled in memory so that each lane's
+// 16-byte load is directly an MFMA A operand (1 KiB coalesced per wavefront load, no LDS):
 //   S^T[keys, queries] = K[keys, dh] * Q^T          (v_mfma_f32_32x32x16_bf16)
 //   O^T[dh, queries]  += V^T[dh, keys] * P^T[keys, queries]
 // With keys as the MFMA row dimension each lane holds one query column, so the online
@@ -11,8 +12,14 @@
 // are, after conversion to bf16, exactly the B operand of the second product (the V
 // tiling stores keys in the order in which S^T leaves them in the registers).
 // The ancestor bit rows mask only the blocks that overlap the tree's own slots.
-// Every wavefront writes an un-normalised partial (m, l, O); a second kernel merges
-// the partials of a row in a fixed order.
+// The next block's K is requested while the current block's P*V runs and its V while
+// the next S^T runs, so no second set of registers is needed.
+// The wavefronts of a workgroup merge their (m, l, O) through LDS in a fixed tree.  If
+// the workgroup covers the whole sequence it writes the normalised rows; otherwise it
+// writes an un-normalised partial and a second, small kernel merges the partials of a
+// row in split order.  (Merging inside the same launch by "last workgroup to arrive"
+// needs device-scope fences; on this multi-die part each of them writes back and
+// invalidates a whole L2, which measured 3-4x the cost of the separate launch.)
 #include "common.h"
 #include "kernels.h"
 
@@ -27,82 +34,107 @@ struct AttnArgs {
   const int32_t* kv_off;
   const int32_t* prefix_len;
   const int32_t* status_dev;
-  int n_heads, s_pool, bpw, nsplit_max, qg_max;
+  int n_heads, s_pool, bpwg, nsplit_max, qg_max;
   float scale_log2e;
-  float* po;  // [T][H][nsplit_max][DH]
-  float* pm;  // [T][H][nsplit_max]
-  float* pl;
+  float* po;        // [T][H][nsplit_max][DH] un-normalised partial outputs
+  float* pm;        // [T][H][nsplit_max] running max (log2 domain)
+  float* pl;        // [T][H][nsplit_max] sum of weights
+  uint16_t* out;
+  int tiled, tp;
 };
 
 constexpr float NEG_BIG = -1e30f;
+constexpr int ATTN_WAVES = 8;
 
-template <int DH, int NQT>
-__global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnArgs a) {
-  constexpr int KS = DH / 16, MTV = DH / 32;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+template <int DH>
+__device__ inline void attn_store_row(const AttnArgs& a, int t, int head, int c, u32x2 v) {
+  uint16_t* dst = a.tiled ? a.out + a_off(t, head * DH + c, a.tp)
+                          : a.out + ((size_t)t * a.n_heads + head) * DH + c;
+  *reinterpret_cast<u32x2*>(dst) = v;
+}
+
+template <int DH, int NTW>
+__global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArgs a) {
+  constexpr int KS = ATTN_WAVES / NTW, KSTEPS = DH / 16, MTV = DH / 32;
+  constexpr int OW = MTV * 16 * 64;  // floats of one wavefront's O tile
+  extern __shared__ __align__(16) float red[];  // KS/2 * NTW * OW floats
+  __shared__ float sm_m[ATTN_WAVES][32], sm_l[ATTN_WAVES][32];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nt = wv % NTW, ks = wv / NTW;
   const int head = blockIdx.y, s = blockIdx.z;
-  if (a.status_dev[s] != 0) return;
+  if (a.status_dev[s] != 0) return;  // uniform over the workgroup, before any barrier
   const int r0 = a.node_off[s], n = a.node_off[s + 1] - r0;
   const int L = a.prefix_len[s];
   const int total = L + n;
   const int nb = (total + 31) >> 5;
-  const int nsplit = (nb + a.bpw - 1) / a.bpw;
-  const int wv = blockIdx.x * 4 + w;
-  const int qg = wv % a.qg_max, ks = wv / a.qg_max;
-  if (ks >= nsplit || qg * 32 * NQT >= n) return;  // whole wavefront leaves; no barriers below
-  const int b0 = ks * a.bpw, b1 = min(nb, b0 + a.bpw);
+  const int nsplit = (nb + a.bpwg - 1) / a.bpwg;
+  const int qg = blockIdx.x % a.qg_max, sp = blockIdx.x / a.qg_max;
+  if (sp >= nsplit || qg * 32 * NTW >= n) return;  // uniform as well
+  const int b0 = sp * a.bpwg, b1 = min(nb, b0 + a.bpwg);
   const int n32 = lane & 31, hh = lane >> 5;
 
-  // queries of this wavefront: B operands of the first product, kept in registers
-  bf16x8 qreg[NQT][KS];
-  uint64_t anc0[NQT], anc1[NQT];
-  int qrow[NQT];
-#pragma unroll
-  for (int nt = 0; nt < NQT; ++nt) {
-    int qi = (qg * NQT + nt) * 32 + n32;
-    bool valid = qi < n;
-    qrow[nt] = valid ? r0 + qi : -1;
+  // this wavefront's 32 queries: B operands of the first product, kept in registers
+  const int qi = (qg * NTW + nt) * 32 + n32;
+  const bool valid = qi < n;
+  const int qrow = valid ? r0 + qi : -1;
+  bf16x8 qreg[KSTEPS];
+  {
     const uint16_t* qp = a.q + ((size_t)(r0 + (valid ? qi : 0)) * a.n_heads + head) * DH + hh * 8;
 #pragma unroll
-    for (int k = 0; k < KS; ++k) {
+    for (int k = 0; k < KSTEPS; ++k) {
       u32x4 v = {0, 0, 0, 0};
       if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * k);
-      qreg[nt][k] = __builtin_bit_cast(bf16x8, v);
+      qreg[k] = __builtin_bit_cast(bf16x8, v);
     }
-    anc0[nt] = valid ? a.anc[2 * (size_t)(r0 + qi)] : 0;
-    anc1[nt] = valid ? a.anc[2 * (size_t)(r0 + qi) + 1] : 0;
   }
+  const uint64_t anc0 = valid ? a.anc[2 * (size_t)(r0 + qi)] : 0;
+  const uint64_t anc1 = valid ? a.anc[2 * (size_t)(r0 + qi) + 1] : 0;
 
-  f32x16 o[NQT][MTV];
-  float m[NQT], l[NQT];
+  f32x16 o[MTV];
 #pragma unroll
-  for (int nt = 0; nt < NQT; ++nt) {
-    m[nt] = NEG_BIG;
-    l[nt] = 0.f;
+  for (int mt = 0; mt < MTV; ++mt)
 #pragma unroll
-    for (int mt = 0; mt < MTV; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[nt][mt][v] = 0.f;
-  }
+    for (int v = 0; v < 16; ++v) o[mt][v] = 0.f;
+  float m = NEG_BIG, l = 0.f;
 
   const size_t plane = (size_t)head * a.s_pool * DH;
   const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_layer + plane) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_layer + plane) + lane;
   const int blk_base = a.kv_off[s] >> 5;
-
-  for (int b = b0; b < b1; ++b) {
-    const u32x4* kb = kp + (size_t)(blk_base + b) * KS * 64;
-    const u32x4* vb = vp + (size_t)(blk_base + b) * MTV * 2 * 64;
-    u32x4 kreg[KS], vreg[MTV][2];
+  u32x4 kreg[KSTEPS], vreg[MTV][2];
+  auto load_k = [&](int b) {
+    const u32x4* kb = kp + (size_t)(blk_base + b) * KSTEPS * 64;
 #pragma unroll
-    for (int k = 0; k < KS; ++k) kreg[k] = kb[k * 64];
+    for (int k = 0; k < KSTEPS; ++k) kreg[k] = kb[k * 64];
+  };
+  auto load_v = [&](int b) {
+    const u32x4* vb = vp + (size_t)(blk_base + b) * MTV * 2 * 64;
 #pragma unroll
     for (int mt = 0; mt < MTV; ++mt)
 #pragma unroll
       for (int kg = 0; kg < 2; ++kg) vreg[mt][kg] = vb[(mt * 2 + kg) * 64];
+  };
 
+  int b = b0 + ks;
+  if (b < b1) {
+    load_k(b);
+    load_v(b);
+  }
+  for (; b < b1; b += KS) {
     const int key0 = b * 32;
     const bool need_mask = key0 + 32 > L;
+    f32x16 sacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+    for (int k = 0; k < KSTEPS; ++k)
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[k]), qreg[k],
+                                                     sacc, 0, 0, 0);
+    const int bn = b + KS;
+    if (bn < b1) load_k(bn);  // uniform branch; in flight during the softmax and P*V
+
     if (key0 + 32 > total) {
       // slots past the sequence's last row may hold anything (NaN bit patterns too):
       // clear them in the V operand, their probabilities are exactly zero
@@ -118,149 +150,212 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnArgs a) {
           }
         }
     }
-
+    float sv[16];
+    float mx = NEG_BIG;
 #pragma unroll
-    for (int nt = 0; nt < NQT; ++nt) {
-      f32x16 sacc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-      for (int k = 0; k < KS; ++k)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[k]),
-                                                       qreg[nt][k], sacc, 0, 0, 0);
-      float sv[16];
-      float mx = NEG_BIG;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        bool vis = true;
-        if (need_mask) {
-          int kk = key0 + 8 * (v >> 2) + 4 * hh + (v & 3);
-          if (kk >= L) {
-            int j = kk - L;
-            vis = j < 64 ? ((anc0[nt] >> j) & 1) : (j < 128 ? ((anc1[nt] >> (j - 64)) & 1) : 0);
-          }
+    for (int v = 0; v < 16; ++v) {
+      bool vis = true;
+      if (need_mask) {
+        int kk = key0 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        if (kk >= L) {
+          int j = kk - L;
+          vis = j < 64 ? ((anc0 >> j) & 1) : (j < 128 ? ((anc1 >> (j - 64)) & 1) : 0);
         }
-        sv[v] = vis ? sacc[v] * a.scale_log2e : NEG_BIG;
-        mx = fmaxf(mx, sv[v]);
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m[nt], mx);
-      const float alpha = exp2f(m[nt] - m_new);
-      float lsum = 0.f;
-      float p[16];
+      sv[v] = vis ? sacc[v] * a.scale_log2e : NEG_BIG;
+      mx = fmaxf(mx, sv[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = exp2f(m - m_new);
+    float lsum = 0.f;
+    float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p[v] = sv[v] > -1e29f ? exp2f(sv[v] - m_new) : 0.f;
-        lsum += p[v];
-      }
-      l[nt] = l[nt] * alpha + lsum;
-      m[nt] = m_new;
-      u32x4 pk[2];
+    for (int v = 0; v < 16; ++v) {
+      p[v] = sv[v] > -1e29f ? exp2f(sv[v] - m_new) : 0.f;
+      lsum += p[v];
+    }
+    l = l * alpha + lsum;
+    m = m_new;
+    u32x4 pk[2];
+#pragma unroll
+    for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pk[kg][e] = pack2bf(p[8 * kg + 2 * e], p[8 * kg + 2 * e + 1]);
+#pragma unroll
+    for (int mt = 0; mt < MTV; ++mt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mt][v] *= alpha;
 #pragma unroll
       for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pk[kg][e] = pack2bf(p[8 * kg + 2 * e], p[8 * kg + 2 * e + 1]);
-#pragma unroll
-      for (int mt = 0; mt < MTV; ++mt) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[nt][mt][v] *= alpha;
-#pragma unroll
-        for (int kg = 0; kg < 2; ++kg)
-          o[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, vreg[mt][kg]), __builtin_bit_cast(bf16x8, pk[kg]),
-              o[nt][mt], 0, 0, 0);
-      }
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[mt][kg]),
+                                                        __builtin_bit_cast(bf16x8, pk[kg]), o[mt],
+                                                        0, 0, 0);
     }
+    if (bn < b1) load_v(bn);  // in flight during the next S^T and softmax
   }
 
-  // partial results of this wavefront
+  // ---- merge the KS key streams of every query tile (fixed order, deterministic)
+  const float lt = l + __shfl_xor(l, 32);
+  if (hh == 0) {
+    sm_m[wv][n32] = m;
+    sm_l[wv][n32] = lt;
+  }
+  __syncthreads();
+  float mg = NEG_BIG;
 #pragma unroll
-  for (int nt = 0; nt < NQT; ++nt) {
-    float lt = l[nt] + __shfl_xor(l[nt], 32);
-    if (qrow[nt] < 0) continue;
-    size_t pidx = ((size_t)qrow[nt] * a.n_heads + head) * a.nsplit_max + ks;
+  for (int k = 0; k < KS; ++k) mg = fmaxf(mg, sm_m[nt + NTW * k][n32]);
+  float lg = 0.f;
+#pragma unroll
+  for (int k = 0; k < KS; ++k) lg += sm_l[nt + NTW * k][n32] * exp2f(sm_m[nt + NTW * k][n32] - mg);
+  {
+    const float sc = exp2f(m - mg);
+#pragma unroll
+    for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mt][v] *= sc;
+  }
+#pragma unroll
+  for (int step = KS / 2; step >= 1; step >>= 1) {
+    if (ks >= step && ks < 2 * step) {
+      float* dst = red + ((ks - step) * NTW + nt) * OW + lane;
+#pragma unroll
+      for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dst[(mt * 16 + v) * 64] = o[mt][v];
+    }
+    __syncthreads();
+    if (ks < step) {
+      const float* src = red + (ks * NTW + nt) * OW + lane;
+#pragma unroll
+      for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[mt][v] += src[(mt * 16 + v) * 64];
+    }
+    __syncthreads();
+  }
+
+  if (nsplit == 1) {
+    // the workgroup saw every key: write the normalised rows
+    if (ks == 0 && qrow >= 0) {
+      const float inv = 1.0f / lg;
+#pragma unroll
+      for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 v = {pack2bf(o[mt][4 * g] * inv, o[mt][4 * g + 1] * inv),
+                     pack2bf(o[mt][4 * g + 2] * inv, o[mt][4 * g + 3] * inv)};
+          attn_store_row<DH>(a, qrow, head, 32 * mt + 8 * g + 4 * hh, v);
+        }
+    }
+    return;
+  }
+
+  // ---- un-normalised partial of this workgroup (merged by attn_combine_kernel)
+  if (ks == 0 && qrow >= 0) {
+    size_t pidx = ((size_t)qrow * a.n_heads + head) * a.nsplit_max + sp;
     if (hh == 0) {
-      a.pm[pidx] = m[nt];
-      a.pl[pidx] = lt;
+      a.pm[pidx] = mg;
+      a.pl[pidx] = lg;
     }
     float* orow = a.po + pidx * DH;
 #pragma unroll
     for (int mt = 0; mt < MTV; ++mt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        f32x4 v = {o[nt][mt][4 * g], o[nt][mt][4 * g + 1], o[nt][mt][4 * g + 2],
-                   o[nt][mt][4 * g + 3]};
+        f32x4 v = {o[mt][4 * g], o[mt][4 * g + 1], o[mt][4 * g + 2], o[mt][4 * g + 3]};
         *reinterpret_cast<f32x4*>(orow + 32 * mt + 8 * g + 4 * hh) = v;
       }
   }
 }
 
-// Merge the partials of every (row, head) in split order; one thread per 8 columns.
-// tiled != 0: bf16 output in the tiled activation layout (rows t >= T zero filled),
-// else plain [T][H][DH].
+// Merge the partials of every (row, head) in split order; one thread per 8 columns.  The
+// loads of a batch of splits are all issued together (clamped, never predicated).
 template <int DH>
-__global__ __launch_bounds__(256) void attn_combine_kernel(
-    const float* __restrict__ po, const float* __restrict__ pm, const float* __restrict__ pl,
-    const int32_t* __restrict__ row_seq, const int32_t* __restrict__ node_off,
-    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ status_dev, int T,
-    int n_heads, int bpw, int nsplit_max, int tiled, int tp, uint16_t* __restrict__ out) {
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, const int32_t* row_seq,
+                                                           int T) {
+  constexpr int CB = 8;
   const int t = blockIdx.x;
   const int gcol = blockIdx.y * 256 + threadIdx.x;
-  const int ncol = n_heads * DH;
-  if (gcol * 8 >= ncol) return;
+  if (gcol * 8 >= a.n_heads * DH) return;
   const int head = gcol * 8 / DH, c = gcol * 8 % DH;
-  u32x4 res = {0, 0, 0, 0};
-  int s = t < T ? row_seq[t] : -1;
-  if (s >= 0 && status_dev[s] == 0) {
-    int n = node_off[s + 1] - node_off[s];
-    int nb = (prefix_len[s] + n + 31) >> 5;
-    int nsplit = (nb + bpw - 1) / bpw;
-    size_t base = ((size_t)t * n_heads + head) * nsplit_max;
-    float mg = NEG_BIG;
-    for (int k = 0; k < nsplit; ++k) mg = fmaxf(mg, pm[base + k]);
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    float lsum = 0.f;
-    for (int k = 0; k < nsplit; ++k) {
-      float wgt = exp2f(pm[base + k] - mg);
-      lsum += wgt * pl[base + k];
-      const float* pr = po + (base + k) * DH + c;
-      f32x4 x0 = *reinterpret_cast<const f32x4*>(pr), x1 = *reinterpret_cast<const f32x4*>(pr + 4);
+  const int s = row_seq[t];
+  if (s < 0 || a.status_dev[s] != 0) return;  // rows of malformed sequences stay zero
+  const int n = a.node_off[s + 1] - a.node_off[s];
+  const int nb = (a.prefix_len[s] + n + 31) >> 5;
+  const int nsplit = (nb + a.bpwg - 1) / a.bpwg;
+  if (nsplit == 1) return;  // written by the attention kernel itself
+  const size_t base = ((size_t)t * a.n_heads + head) * a.nsplit_max;
+  float mrun = NEG_BIG, lrun = 0.f;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int k0 = 0; k0 < nsplit; k0 += CB) {
+    float ms[CB], ls[CB];
+    f32x4 x0[CB], x1[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      const int k = min(k0 + j, nsplit - 1);
+      ms[j] = a.pm[base + k];
+      ls[j] = a.pl[base + k];
+      const float* pr = a.po + (base + k) * DH + c;
+      x0[j] = *reinterpret_cast<const f32x4*>(pr);
+      x1[j] = *reinterpret_cast<const f32x4*>(pr + 4);
+    }
+    float mb = mrun;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) mb = fmaxf(mb, ms[j]);
+    const float resc = exp2f(mrun - mb);
+    lrun *= resc;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= resc;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      const float wgt = k0 + j < nsplit ? exp2f(ms[j] - mb) : 0.f;
+      lrun += wgt * ls[j];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        acc[e] += wgt * x0[e];
-        acc[4 + e] += wgt * x1[e];
+        acc[e] += wgt * x0[j][e];
+        acc[4 + e] += wgt * x1[j][e];
       }
     }
-    float inv = 1.0f / lsum;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) res[e] = pack2bf(acc[2 * e] * inv, acc[2 * e + 1] * inv);
-  } else if (t < T && !tiled) {
-    // rows of malformed sequences: zeros
+    mrun = mb;
   }
-  if (tiled) {
-    *reinterpret_cast<u32x4*>(out + a_off(t, gcol * 8, tp)) = res;
-  } else if (t < T) {
-    *reinterpret_cast<u32x4*>(out + (size_t)t * ncol + gcol * 8) = res;
-  }
+  const float inv = 1.0f / lrun;
+  attn_store_row<DH>(a, t, head, c, u32x2{pack2bf(acc[0] * inv, acc[1] * inv), pack2bf(acc[2] * inv, acc[3] * inv)});
+  attn_store_row<DH>(a, t, head, c + 4, u32x2{pack2bf(acc[4] * inv, acc[5] * inv), pack2bf(acc[6] * inv, acc[7] * inv)});
 }
 
-void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* nqt, int* qg_max, int* bpw,
+// zero fill (rows of malformed sequences and the padding rows of the tiled output)
+__global__ void zero_u32_kernel(uint32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+int launch_zero_bytes(void* p, size_t bytes, hipStream_t st) {
+  size_t n = bytes / 4;
+  if (n == 0) return TRJ_OK;
+  zero_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((uint32_t*)p, n);
+  return check_launch();
+}
+
+// Launch shape: query tiles per workgroup, query groups, blocks per workgroup, splits.
+void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int* qg_max, int* bpwg,
                     int* nsplit_max) {
   int nmax = T < TRJ_N_MAX ? T : TRJ_N_MAX;
-  *nqt = nmax <= 32 ? 1 : 2;
-  *qg_max = (nmax + 32 * *nqt - 1) / (32 * *nqt);
+  *ntw = nmax <= 32 ? 1 : 2;
+  *qg_max = (nmax + 32 * *ntw - 1) / (32 * *ntw);
+  const int ks = ATTN_WAVES / *ntw;
   int nb = (max_seq_slots + 31) / 32;
   if (nb < 1) nb = 1;
-  long waves_per_block_col = (long)B * n_heads * *qg_max;
-  int b = (int)((nb * waves_per_block_col + g_tune.attn_target_waves - 1) / g_tune.attn_target_waves);
-  if (b < g_tune.attn_min_bpw) b = g_tune.attn_min_bpw;
+  long cols = (long)B * n_heads * *qg_max;
+  int b = (int)((nb * cols + g_tune.attn_target_wgs - 1) / g_tune.attn_target_wgs);
+  if (b < g_tune.attn_min_bpw * ks) b = g_tune.attn_min_bpw * ks;
   if (b > nb) b = nb;
-  *bpw = b;
+  *bpwg = b;
   *nsplit_max = (nb + b - 1) / b;
 }
 
 size_t attn_bf16_ws_floats(int T, int n_heads, int dh, int nsplit_max) {
-  return (size_t)T * n_heads * nsplit_max * (dh + 2);
+  // partials: none needed when every sequence fits one workgroup
+  return nsplit_max > 1 ? (size_t)T * n_heads * nsplit_max * (dh + 2) : 64;
 }
 
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
@@ -270,35 +365,39 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
                           int max_seq_slots, float scale, float* ws, int tiled, int tp,
                           uint16_t* out, hipStream_t st) {
   if (dh != 64 && dh != 128) return TRJ_ERR_BAD_SHAPE;
-  int nqt, qg_max, bpw, nsplit_max;
-  attn_bf16_plan(B, T, n_heads, max_seq_slots, &nqt, &qg_max, &bpw, &nsplit_max);
-  size_t rows = (size_t)T * n_heads * nsplit_max;
+  int ntw, qg_max, bpwg, nsplit_max;
+  attn_bf16_plan(B, T, n_heads, max_seq_slots, &ntw, &qg_max, &bpwg, &nsplit_max);
+  size_t rows = nsplit_max > 1 ? (size_t)T * n_heads * nsplit_max : 0;
   float* po = ws;
   float* pm = ws + rows * dh;
   float* pl = pm + rows;
   AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, s_pool,
-             bpw, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl};
-  int waves = nsplit_max * qg_max;
-  dim3 grid((waves + 3) / 4, n_heads, B);
-#define TRJ_ATTN(D, Q) tree_attn_bf16_kernel<D, Q><<<grid, 256, 0, st>>>(a)
-  prof_begin(KC_ATTN, st);
-  if (dh == 128) { if (nqt == 1) TRJ_ATTN(128, 1); else TRJ_ATTN(128, 2); }
-  else { if (nqt == 1) TRJ_ATTN(64, 1); else TRJ_ATTN(64, 2); }
+             bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, out, tiled, tp};
+  dim3 grid(nsplit_max * qg_max, n_heads, B);
+  const int ks = ATTN_WAVES / ntw;
+  size_t lds = (size_t)(ks / 2) * ntw * (dh / 32) * 16 * 64 * sizeof(float);
+  {
+    ProfScope ps_(KC_ATTN, st);
+#define TRJ_ATTN(D, Q)                                                                        \
+  do {                                                                                        \
+    static bool big_lds_allowed = false; /* one-time, per instantiation */                    \
+    if (!big_lds_allowed) {                                                                   \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tree_attn_bf16_kernel<D, Q>),   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);      \
+      big_lds_allowed = true;                                                                 \
+    }                                                                                         \
+    tree_attn_bf16_kernel<D, Q><<<grid, ATTN_WAVES * 64, lds, st>>>(a);                       \
+  } while (0)
+    if (dh == 128) { if (ntw == 1) TRJ_ATTN(128, 1); else TRJ_ATTN(128, 2); }
+    else { if (ntw == 1) TRJ_ATTN(64, 1); else TRJ_ATTN(64, 2); }
 #undef TRJ_ATTN
-  prof_end(KC_ATTN, st);
+  }
   int rc = check_launch();
-  if (rc) return rc;
-  int rows_out = tiled ? tp : T;
-  dim3 cgrid(rows_out, (n_heads * dh / 8 + 255) / 256);
+  if (rc || nsplit_max == 1) return rc;
   ProfScope ps_(KC_ATTN_COMBINE, st);
-  if (dh == 128)
-    attn_combine_kernel<128><<<cgrid, 256, 0, st>>>(po, pm, pl, row_seq, node_off, prefix_len,
-                                                    status_dev, T, n_heads, bpw, nsplit_max, tiled,
-                                                    tp, out);
-  else
-    attn_combine_kernel<64><<<cgrid, 256, 0, st>>>(po, pm, pl, row_seq, node_off, prefix_len,
-                                                   status_dev, T, n_heads, bpw, nsplit_max, tiled,
-                                                   tp, out);
+  dim3 cgrid(T, (n_heads * dh / 8 + 255) / 256);
+  if (dh == 128) attn_combine_kernel<128><<<cgrid, 256, 0, st>>>(a, row_seq, T);
+  else attn_combine_kernel<64><<<cgrid, 256, 0, st>>>(a, row_seq, T);
   return check_launch();
 }
 

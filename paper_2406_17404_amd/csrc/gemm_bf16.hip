@@ -271,8 +271,12 @@ static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, in
   size_t lds_x = (size_t)2 * PH * MT * 1024, lds_r = (size_t)(KW - 1) * RT * MT * 4096;
   size_t lds = lds_x > lds_r ? lds_x : lds_r;
   auto kern = gemm_p_kernel<MT, RT, KW, PH, PF, Epi>;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  static bool big_lds_allowed = false;  // one-time, per instantiation
+  if (!big_lds_allowed) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    big_lds_allowed = true;
+  }
   kern<<<grid, RT * KW * 64, lds, st>>>(a, epi);
 }
 

@@ -9,7 +9,7 @@ struct Tunables {
   int gemm_target_wgs = 256;   // split-k is raised until a GEMM has this many workgroups
   int max_split_k = 8;
   int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..3 force one
-  int attn_target_waves = 1024;
+  int attn_target_wgs = 1024;  // upper bound on attention workgroups per launch
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
 extern Tunables g_tune;
@@ -85,9 +85,10 @@ int launch_sum_splits(const float* partial, int n_split, size_t n, float* y, hip
 int launch_tile_activation(const uint16_t* x, int T, int n, int tp, uint16_t* xp, hipStream_t st);
 
 // attn_bf16.hip
-void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* nqt, int* qg_max, int* bpw,
+void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int* qg_max, int* bpwg,
                     int* nsplit_max);
 size_t attn_bf16_ws_floats(int T, int n_heads, int dh, int nsplit_max);
+int launch_zero_bytes(void* p, size_t bytes, hipStream_t st);
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
                           const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,

@@ -94,13 +94,13 @@ def test_bf16_launch_shapes_give_the_same_answer():
     c = case(21, H, dh, L, n, "bf16")
     want = O.tree_attention(*c)
     try:
-        for waves, bpw in ((64, 1), (4096, 1), (1024, 7), (1, 1)):
-            b.trj_set_tunable("attn_target_waves", waves)
+        for wgs, bpw in ((64, 1), (4096, 1), (1024, 7), (1, 1)):   # one workgroup per head ... 13 splits
+            b.trj_set_tunable("attn_target_wgs", wgs)
             b.trj_set_tunable("attn_min_bpw", bpw)
             got = run_attention("bf16", H, dh, [c])[0]
             assert rel_err(got, want) <= 1e-2
     finally:
-        b.trj_set_tunable("attn_target_waves", 1024)
+        b.trj_set_tunable("attn_target_wgs", 1024)
         b.trj_set_tunable("attn_min_bpw", 2)
 
 
