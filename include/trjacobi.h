@@ -154,6 +154,10 @@ int32_t trj_set_tunable(const char* name, int32_t value);
 int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity);
 int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count);
 
+/* Measurement aid: a plain copy of `bytes` (a multiple of 16) from src to dst, used to
+ * calibrate the HBM traffic counters against a kernel whose traffic is known. */
+int32_t trj_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Tree bookkeeping: depth[i] = depth[parent[i]] + 1 (root 0) and the ancestor-or-self
  * bit rows of the sparse tree mask (appendix "Templates for Token Tree"): bit j%64 of
  * anc[i][j/64] is set when node j is on the path root..i.  A sequence whose tree is

@@ -55,6 +55,7 @@ _SIGS = {
     "trj_set_tunable": (_i32, [C.c_char_p, _i32]),
     "trj_profile_begin": (_i32, [_i32, _i32]),
     "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
+    "trj_copy_probe": (_i32, [_vp, _vp, _sz, _vp]),
     "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
     "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "trj_kv_pack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -137,6 +138,10 @@ def trj_profile_end(capacity: int) -> List[float]:
     n = _i32(0)
     _check("trj_profile_end", lib().trj_profile_end(buf, capacity, C.byref(n)))
     return [float(buf[i]) for i in range(n.value)]
+
+
+def trj_copy_probe(dst, src, nbytes: int) -> None:
+    _check("trj_copy_probe", lib().trj_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream()))
 
 
 def trj_workspace_bytes(desc: ModelDesc, t_max: int, b_max: int, l_max: int) -> int:

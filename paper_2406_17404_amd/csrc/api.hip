@@ -248,6 +248,20 @@ int32_t trj_kv_unpack(void* k_plain, void* v_plain, const void* k_pool, const vo
                     n_heads, head_dim, s_pool, slot0, n_slots, dtype, false, stream);
 }
 
+// Plain device-to-device copy kernel of a known size: the yardstick against which the
+// HBM traffic counters (FETCH_SIZE / WRITE_SIZE) of the other kernels are scaled.
+__global__ void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+int32_t trj_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return TRJ_ERR_NULLPTR;
+  if (bytes == 0 || (bytes & 15)) return TRJ_ERR_BAD_SHAPE;
+  copy_probe_kernel<<<4096, 256, 0, (hipStream_t)stream>>>((const uint4*)src, (uint4*)dst, bytes / 16);
+  return check_launch();
+}
+
 int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B, int32_t T,
                       int32_t* depth, uint64_t* anc, int32_t* status_dev, void* stream) {
   if (!parent || !node_off || !depth || !anc || !status_dev) return TRJ_ERR_NULLPTR;
