@@ -358,7 +358,7 @@ int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_
 // One workgroup per token row: x[t] += sum_s partial[s][t] (fixed order), then
 // h = x * g / sqrt(mean(x^2) + eps) written bf16 in the tiled activation layout.  Rows
 // t >= T of the padded tile are written as zeros.  n_split == 0: norm only.
-constexpr int RN_THREADS = 256, RN_MAXG = 4;
+constexpr int RN_THREADS = 512, RN_MAXG = 2, RN_SB = 8;
 __global__ __launch_bounds__(RN_THREADS) void reduce_norm_kernel(
     const float* __restrict__ partial, int n_split, size_t split_stride, float* __restrict__ x,
     const float* __restrict__ g, int T, int d, int tp, float eps, uint16_t* __restrict__ hp) {
@@ -370,29 +370,44 @@ __global__ __launch_bounds__(RN_THREADS) void reduce_norm_kernel(
       *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = z;
     return;
   }
+  // the kernel is a latency chain (load, add, reduce, store): every load of a thread is
+  // issued before the first one is used, splits in batches of RN_SB with clamped indices
   float vals[RN_MAXG][8];
+  f32x4 gg[RN_MAXG][2];
   float ss = 0.f;
 #pragma unroll
   for (int it = 0; it < RN_MAXG; ++it) {
-    int gi = it * RN_THREADS + tid;
-    if (gi < ngran) {
-      float* xr = x + (size_t)t * d + gi * 8;
-      f32x4 a = *reinterpret_cast<f32x4*>(xr), b = *reinterpret_cast<f32x4*>(xr + 4);
-      for (int s = 0; s < n_split; ++s) {
-        const float* pr = partial + s * split_stride + (size_t)t * d + gi * 8;
-        a += *reinterpret_cast<const f32x4*>(pr);
-        b += *reinterpret_cast<const f32x4*>(pr + 4);
-      }
-      if (n_split > 0) {
-        *reinterpret_cast<f32x4*>(xr) = a;
-        *reinterpret_cast<f32x4*>(xr + 4) = b;
+    const int gi = min(it * RN_THREADS + tid, ngran - 1);
+    const bool live = it * RN_THREADS + tid < ngran;
+    float* xr = x + (size_t)t * d + gi * 8;
+    f32x4 a = *reinterpret_cast<f32x4*>(xr), b = *reinterpret_cast<f32x4*>(xr + 4);
+    gg[it][0] = *reinterpret_cast<const f32x4*>(g + gi * 8);
+    gg[it][1] = *reinterpret_cast<const f32x4*>(g + gi * 8 + 4);
+    for (int s0 = 0; s0 < n_split; s0 += RN_SB) {
+      f32x4 pa[RN_SB], pb[RN_SB];
+#pragma unroll
+      for (int j = 0; j < RN_SB; ++j) {
+        const float* pr = partial + min(s0 + j, n_split - 1) * split_stride + (size_t)t * d + gi * 8;
+        pa[j] = *reinterpret_cast<const f32x4*>(pr);
+        pb[j] = *reinterpret_cast<const f32x4*>(pr + 4);
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vals[it][e] = a[e];
-        vals[it][4 + e] = b[e];
-        ss += a[e] * a[e] + b[e] * b[e];
+      for (int j = 0; j < RN_SB; ++j) {
+        if (s0 + j < n_split) {  // same order for every launch: s = 0, 1, ...
+          a += pa[j];
+          b += pb[j];
+        }
       }
+    }
+    if (n_split > 0 && live) {
+      *reinterpret_cast<f32x4*>(xr) = a;
+      *reinterpret_cast<f32x4*>(xr + 4) = b;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vals[it][e] = a[e];
+      vals[it][4 + e] = b[e];
+      if (live) ss += a[e] * a[e] + b[e] * b[e];
     }
   }
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
@@ -407,11 +422,14 @@ __global__ __launch_bounds__(RN_THREADS) void reduce_norm_kernel(
   for (int it = 0; it < RN_MAXG; ++it) {
     int gi = it * RN_THREADS + tid;
     if (gi < ngran) {
-      const float* gg = g + gi * 8;
       u32x4 pk;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        pk[e] = pack2bf(vals[it][2 * e] * gg[2 * e] * inv, vals[it][2 * e + 1] * gg[2 * e + 1] * inv);
+      for (int e = 0; e < 2; ++e) {
+        pk[e] = pack2bf(vals[it][2 * e] * gg[it][0][2 * e] * inv,
+                        vals[it][2 * e + 1] * gg[it][0][2 * e + 1] * inv);
+        pk[2 + e] = pack2bf(vals[it][4 + 2 * e] * gg[it][1][2 * e] * inv,
+                            vals[it][4 + 2 * e + 1] * gg[it][1][2 * e + 1] * inv);
+      }
       *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = pk;
     }
   }

@@ -140,6 +140,31 @@ def test_packed_bf16_batch_with_ragged_prefixes():
     run_and_check(shape, w, trees, toks, Ls, pkvs, 1e-2)
 
 
+def test_packed_16_sequences_of_64_nodes():
+    """The packed workload's structure (16 sequences, 64-node random trees, ragged prefixes
+    U[256, 4096], 1024 tree rows in one launch) on a shrunken 2-layer model."""
+    shape = I.ModelShape(2, 512, 4, 128, 1408, 1024, "bf16")
+    w = I.gen_weights(shape, 1004)
+    wl = I.workload("C4")
+    trees = I.gen_trees(wl)
+    Ls = list(wl.prefix_len)
+    toks = [I.gen_tokens(shape.vocab, 64, 1004, "tree", s) for s in range(16)]
+    pkvs = [prefix_normal(shape, 1004, s, Ls[s]) for s in range(16)]
+    res, summary = run_and_check(shape, w, trees, toks, Ls, pkvs, 1e-2)
+    print("packed 16x64: worst logits rel err %.2e" % max(e for e, _, _ in summary))
+
+
+def test_long_prefix_128_node_tree():
+    """The code-model workload's structure (prefix 4096, 128-node tree: chain of 16 plus
+    retrieval branches) on a shrunken 2-layer model."""
+    shape = I.ModelShape(2, 512, 4, 128, 1408, 1024, "bf16")
+    w = I.gen_weights(shape, 1003)
+    tree = I.gen_trees(I.workload("C3"))[0]
+    tok = I.gen_tokens(shape.vocab, 128, 1003, "tree")
+    res, summary = run_and_check(shape, w, [tree], [tok], [4096], [prefix_normal(shape, 1003, 0, 4096)], 1e-2)
+    print("L=4096 N=128: logits rel err %.2e" % summary[0][0])
+
+
 def test_bf16_prefill_consistent_prefix_and_planted_acceptance():
     """bf16 model whose prefix K/V come from its own prefill; drafts planted from the
     brute-force greedy continuation.  Acceptance is checked against the oracle's accept on
