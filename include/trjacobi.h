@@ -219,6 +219,70 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
                        int32_t* path, int32_t* bonus_tok, int32_t* new_len,
                        int32_t* status_dev, void* stream);
 
+/* ---- TR-Jacobi decoding loop (section "TR-Jacobi Decoding") -------------------------
+ * Generation starts from a tree whose nodes are ahead noise (Eq. 4), every round
+ * verifies the tree with tr_verify_step's forward, commits the longest accepted path
+ * plus the greedy token after it, and refills the tree from the predictions made below
+ * the accepted node; one chain below the root carries tokens retrieved by prompt lookup
+ * (paragraph "Retrieval-Augmented Jacobi Decoding").  The committed tokens equal plain
+ * greedy decoding whatever the drafts are.
+ *
+ * Refill rule (the paper only says "the path's subsequent predictions"): the new tree
+ * is laid over the old one with its root on the accepted node; a new node that is the
+ * k-th child (index order) of its parent lies on the k-th child of the old node under
+ * its parent, if there is one, and takes the prediction made there as its token; a new
+ * node that lies on nothing takes ahead noise: ctx[r mod ctx_len] with r the
+ * (step * TRJ_N_MAX + node + 1)-th SplitMix64 output for `seed` and ctx all committed
+ * tokens.  The last retrieval_len nodes of the template must be a chain below the root;
+ * prompt lookup tries suffix lengths max_ngram..1 of ctx, takes the most recent earlier
+ * occurrence and copies up to retrieval_len following tokens over that chain.
+ *
+ * The four helpers below are pure host functions (no GPU is touched). */
+typedef struct {
+  int32_t n_nodes;         /* N, root included, 1..TRJ_N_MAX */
+  const int32_t* h_parent; /* HOST [N]: parent[0] = -1, 0 <= parent[i] < i */
+  int32_t retrieval_len;   /* R in 0..N-1 */
+  int32_t max_ngram;       /* >= 1 */
+  int32_t max_new_tokens;  /* >= 1 */
+  int32_t eos_token;       /* generation stops after this token (kept); -1: never */
+  uint64_t seed;
+} trj_decode_config;
+
+/* k-th output (k >= 1) of SplitMix64 started at state `seed`. */
+uint64_t trj_splitmix64(uint64_t seed, uint64_t k);
+int32_t trj_ahead_noise(const int32_t* h_ctx, int32_t ctx_len, uint64_t seed, int32_t step,
+                        int32_t node, int32_t* h_token);
+/* h_out[0..*h_found) = the retrieved tokens, *h_found <= r. */
+int32_t trj_prompt_lookup(const int32_t* h_ctx, int32_t ctx_len, int32_t max_ngram, int32_t r,
+                          int32_t* h_out, int32_t* h_found);
+/* Tokens of the tree verified in round `step`; ctx's last token is the root.
+ * h_argmax == NULL: first tree (all noise + lookup); else the previous round's
+ * predictions [N] and accepted node `best`. */
+int32_t trj_fill_tree(const int32_t* h_parent, int32_t n_nodes, int32_t retrieval_len,
+                      const int32_t* h_ctx, int32_t ctx_len, int32_t max_ngram, uint64_t seed,
+                      int32_t step, const int32_t* h_argmax, int32_t best, int32_t* h_tok);
+
+/* Device scratch tr_jacobi_generate needs for these sizes and this pool capacity. */
+int32_t tr_jacobi_generate_workspace_bytes(const trj_model_desc* desc, int32_t n_nodes,
+                                           int32_t prompt_len, int32_t max_new_tokens,
+                                           int32_t s_pool, size_t* h_bytes);
+
+/* Greedy generation for ONE sequence whose K/V live at slot 0.. of the pool (kv offset
+ * 0; s_pool slots per head, a multiple of TRJ_KV_BLOCK, at least prompt_len +
+ * max_new_tokens + N).  The prompt's K/V are computed first by chain-shaped trees of up
+ * to TRJ_N_MAX tokens (an ordinary causal forward); the pool's previous contents are
+ * ignored.  h_prompt: HOST [prompt_len], prompt_len >= 1, ids in [0, vocab).  Outputs
+ * (HOST): h_tokens[max_new_tokens], *h_n_tokens, h_accept_hist[max_new_tokens] (accepted
+ * drafts per round, may be NULL), *h_n_steps (rounds).  Synchronous: returns after the
+ * stream has drained.  Errors as above; nothing is written to the host outputs'
+ * token area on an argument error. */
+int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
+                           void* v_pool, size_t kv_layer_stride, int32_t s_pool,
+                           const int32_t* h_prompt, int32_t prompt_len,
+                           const trj_decode_config* cfg, void* workspace, size_t ws_bytes,
+                           int32_t* h_tokens, int32_t* h_n_tokens, int32_t* h_accept_hist,
+                           int32_t* h_n_steps, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,12 @@ class LayerWeights(C.Structure):
                 ("g_ffn", C.c_void_p), ("w_gate_up", C.c_void_p), ("w_down", C.c_void_p)]
 
 
+class DecodeConfig(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("h_parent", C.POINTER(C.c_int32)),
+                ("retrieval_len", C.c_int32), ("max_ngram", C.c_int32),
+                ("max_new_tokens", C.c_int32), ("eos_token", C.c_int32), ("seed", C.c_uint64)]
+
+
 class Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("g_final", C.c_void_p), ("w_lm", C.c_void_p),
                 ("h_layers", C.POINTER(LayerWeights))]
@@ -49,6 +55,7 @@ class Weights(C.Structure):
 
 _lib = None
 _vp, _i32, _sz, _f = C.c_void_p, C.c_int32, C.c_size_t, C.c_float
+_ip = C.POINTER(C.c_int32)
 _SIGS = {
     "trj_version": (C.c_char_p, []),
     "trj_last_hip_error": (_i32, []),
@@ -67,6 +74,15 @@ _SIGS = {
     "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
     "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
                        [_vp] * 5 + [_i32] * 3 + [_vp, _sz] + [_vp] * 9),
+    "trj_splitmix64": (C.c_uint64, [C.c_uint64, C.c_uint64]),
+    "trj_ahead_noise": (_i32, [_ip, _i32, C.c_uint64, _i32, _i32, _ip]),
+    "trj_prompt_lookup": (_i32, [_ip, _i32, _i32, _i32, _ip, _ip]),
+    "trj_fill_tree": (_i32, [_ip, _i32, _i32, _ip, _i32, _i32, C.c_uint64, _i32, _ip, _i32, _ip]),
+    "tr_jacobi_generate_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, _i32,
+                                                  C.POINTER(_sz)]),
+    "tr_jacobi_generate": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32,
+                                  _ip, _i32, C.POINTER(DecodeConfig), _vp, _sz, _ip, _ip, _ip, _ip,
+                                  _vp]),
 }
 
 
@@ -207,6 +223,68 @@ def tr_verify_step(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_layer_s
         max_seq_slots, _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(logits), _ptr(argmax_out), _ptr(accept_len), _ptr(best_node), _ptr(path),
         _ptr(bonus_tok), _ptr(new_len), _ptr(status_dev), _stream()))
+
+
+# ------------------------------------------------------------------ decoding loop
+def _host_i32(values):
+    values = [int(v) for v in values]
+    return (C.c_int32 * max(1, len(values)))(*values), len(values)
+
+
+def trj_splitmix64(seed: int, k: int) -> int:
+    return int(lib().trj_splitmix64(seed, k))
+
+
+def trj_ahead_noise(ctx, seed: int, step: int, node: int) -> int:
+    buf, n = _host_i32(ctx)
+    out = _i32(0)
+    _check("trj_ahead_noise", lib().trj_ahead_noise(buf, n, seed, step, node, C.byref(out)))
+    return out.value
+
+
+def trj_prompt_lookup(ctx, max_ngram: int, r: int) -> List[int]:
+    buf, n = _host_i32(ctx)
+    out = (C.c_int32 * max(1, r))()
+    found = _i32(0)
+    _check("trj_prompt_lookup", lib().trj_prompt_lookup(buf, n, max_ngram, r, out, C.byref(found)))
+    return [int(out[i]) for i in range(found.value)]
+
+
+def trj_fill_tree(parent, retrieval_len: int, ctx, max_ngram: int, seed: int, step: int,
+                  argmax=None, best: int = 0) -> List[int]:
+    pbuf, n = _host_i32(parent)
+    cbuf, nc = _host_i32(ctx)
+    abuf = _host_i32(argmax)[0] if argmax is not None else None
+    tok = (C.c_int32 * n)()
+    _check("trj_fill_tree", lib().trj_fill_tree(pbuf, n, retrieval_len, cbuf, nc, max_ngram, seed,
+                                                step, abuf, best, tok))
+    return [int(t) for t in tok]
+
+
+def tr_jacobi_generate_workspace_bytes(desc: ModelDesc, n_nodes: int, prompt_len: int,
+                                       max_new_tokens: int, s_pool: int) -> int:
+    out = _sz(0)
+    _check("tr_jacobi_generate_workspace_bytes", lib().tr_jacobi_generate_workspace_bytes(
+        C.byref(desc), n_nodes, prompt_len, max_new_tokens, s_pool, C.byref(out)))
+    return out.value
+
+
+def tr_jacobi_generate(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_layer_stride, s_pool,
+                       prompt, parent, retrieval_len, max_ngram, max_new_tokens, eos_token, seed,
+                       workspace):
+    """Returns (tokens, accept_hist, n_steps) as Python lists / int."""
+    pbuf, plen = _host_i32(prompt)
+    tbuf, n = _host_i32(parent)
+    cfg = DecodeConfig(n, tbuf, retrieval_len, max_ngram, max_new_tokens, eos_token, seed)
+    toks = (C.c_int32 * max(1, max_new_tokens))()
+    hist = (C.c_int32 * max(1, max_new_tokens))()
+    n_tok, n_steps = _i32(0), _i32(0)
+    _check("tr_jacobi_generate", lib().tr_jacobi_generate(
+        C.byref(desc), C.byref(weights), _ptr(k_pool), _ptr(v_pool), kv_layer_stride, s_pool, pbuf,
+        plen, C.byref(cfg), _ptr(workspace), workspace.numel() * workspace.element_size(), toks,
+        C.byref(n_tok), hist, C.byref(n_steps), _stream()))
+    return ([int(toks[i]) for i in range(n_tok.value)],
+            [int(hist[i]) for i in range(n_steps.value)], n_steps.value)
 
 
 # ------------------------------------------------------------------ marshalling helpers

@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrjacobi.so")
-SOURCES = ["api.hip", "tree_kernels.hip", "f32_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip"]
+SOURCES = ["api.hip", "tree_kernels.hip", "f32_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip",
+           "decode_loop.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

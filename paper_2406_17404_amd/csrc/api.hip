@@ -362,17 +362,26 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   return launch_sum_splits(part, sk, (size_t)T * n_out, y, st);
 }
 
-int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
-                       void* v_pool, size_t kv_layer_stride, int32_t s_pool, const int32_t* tok,
-                       const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
-                       const int32_t* prefix_len, int32_t B, int32_t T, int32_t max_seq_slots,
-                       void* workspace, size_t ws_bytes, float* logits, int32_t* argmax_out,
-                       int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
-                       int32_t* new_len, int32_t* status_dev, void* stream) {
+}  // extern "C"
+
+namespace trj {
+// The forward pass over the tree rows; with_head == false stops after the last decoder
+// layer (the tree's K/V are in the pool, nothing else is produced), which is what a
+// prompt pass needs.
+int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_pool, void* v_pool,
+              size_t kv_layer_stride, int32_t s_pool, const int32_t* tok, const int32_t* parent,
+              const int32_t* node_off, const int32_t* kv_off, const int32_t* prefix_len,
+              int32_t B, int32_t T, int32_t max_seq_slots, void* workspace, size_t ws_bytes,
+              float* logits, int32_t* argmax_out, int32_t* accept_len, int32_t* best_node,
+              int32_t* path, int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev,
+              bool with_head, hipStream_t st) {
   TRJ_TRY(check_desc(desc));
   if (!weights || !weights->h_layers || !weights->embed || !weights->g_final || !weights->w_lm ||
       !k_pool || !v_pool || !tok || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
-      !argmax_out || !accept_len || !best_node || !path || !bonus_tok || !new_len || !status_dev)
+      !status_dev)
+    return TRJ_ERR_NULLPTR;
+  if (with_head &&
+      (!argmax_out || !accept_len || !best_node || !path || !bonus_tok || !new_len))
     return TRJ_ERR_NULLPTR;
   const trj_model_desc& m = *desc;
   for (int l = 0; l < m.n_layers; ++l) {
@@ -388,10 +397,9 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
 
   Carver c(workspace);
   StepWs w;
-  carve_step(c, m, B, T, max_seq_slots, logits == nullptr, &w);
+  carve_step(c, m, B, T, max_seq_slots, with_head && logits == nullptr, &w);
   if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
   float* lg = logits ? logits : w.logits;
-  hipStream_t st = (hipStream_t)stream;
   const float scale = 1.0f / sqrtf((float)dh);
 
   TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots,
@@ -420,8 +428,10 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
       { ProfScope ps_(KC_GEMM_GATE_UP, st); TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st)); }
       { ProfScope ps_(KC_GEMM_DOWN, st); TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, w.partial, st)); }
       const float* g_next = l + 1 < m.n_layers ? weights->h_layers[l + 1].g_attn : weights->g_final;
+      if (!with_head && l + 1 == m.n_layers) break;  // nothing reads the last FFN of a prompt pass
       { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st)); }
     }
+    if (!with_head) return TRJ_OK;
     { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st)); }
   } else {
     for (int l = 0; l < m.n_layers; ++l) {
@@ -439,6 +449,7 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
       TRJ_TRY(launch_silu_mul_f32(w.gu, T, F, w.actf, st));
       TRJ_TRY(launch_gemm_f32(w.actf, (const float*)lw.w_down, T, F, d, 1, w.x, st));
     }
+    if (!with_head) return TRJ_OK;
     TRJ_TRY(launch_rmsnorm_f32(w.x, weights->g_final, T, d, m.rms_eps, w.h, st));
     TRJ_TRY(launch_gemm_f32(w.h, (const float*)weights->w_lm, T, d, V, 0, lg, st));
   }
@@ -450,4 +461,25 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
                            m.n_layers, H, dh, s_pool, m.dtype, new_len, st);
 }
 
-}  // extern "C"
+// workspace bytes of one step_impl call (pure arithmetic)
+size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_slots) {
+  Carver c(nullptr);
+  StepWs w;
+  carve_step(c, m, B, T, max_seq_slots, true, &w);
+  return c.off + 256;
+}
+int check_model(const trj_model_desc* m) { return check_desc(m); }
+}  // namespace trj
+
+extern "C" int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
+                       void* v_pool, size_t kv_layer_stride, int32_t s_pool, const int32_t* tok,
+                       const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                       const int32_t* prefix_len, int32_t B, int32_t T, int32_t max_seq_slots,
+                       void* workspace, size_t ws_bytes, float* logits, int32_t* argmax_out,
+                       int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* bonus_tok,
+                       int32_t* new_len, int32_t* status_dev, void* stream) {
+  return trj::step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, tok, parent, node_off,
+                        kv_off, prefix_len, B, T, max_seq_slots, workspace, ws_bytes, logits,
+                        argmax_out, accept_len, best_node, path, bonus_tok, new_len, status_dev,
+                        true, (hipStream_t)stream);
+}

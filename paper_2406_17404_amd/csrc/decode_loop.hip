@@ -1,0 +1,306 @@
+// TR-Jacobi decoding loop around the verify step (paper, section "TR-Jacobi Decoding"):
+// host-side integer logic (ahead noise of Eq. 4, prompt lookup for the retrieval path,
+// refill of the tree from the predictions below the accepted node) and the driver that
+// alternates it with the device step.  One host<->device exchange per round: the tree's
+// tokens and the prefix length go in, the predictions and the accepted path come out.
+#include <vector>
+
+#include "kernels.h"
+
+namespace trj {
+
+#define TRJ_TRY(expr)              \
+  do {                             \
+    int rc_ = (expr);              \
+    if (rc_ != TRJ_OK) return rc_; \
+  } while (0)
+#define TRJ_HIP(expr)              \
+  do {                             \
+    hipError_t e_ = (expr);        \
+    if (e_ != hipSuccess) {        \
+      note_hip_error(e_);          \
+      return TRJ_ERR_HIP;          \
+    }                              \
+  } while (0)
+
+// SplitMix64: state seed + k * golden, mixed by two xor-shift-multiply rounds
+static inline uint64_t splitmix64_at(uint64_t seed, uint64_t k) {
+  uint64_t z = seed + 0x9E3779B97F4A7C15ull * k;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+static inline int32_t noise_token(const int32_t* ctx, int32_t ctx_len, uint64_t seed, int32_t step,
+                                  int32_t node) {
+  uint64_t r = splitmix64_at(seed, (uint64_t)step * TRJ_N_MAX + (uint64_t)node + 1);
+  return ctx[r % (uint64_t)ctx_len];
+}
+
+// longest suffix (<= max_ngram tokens) of ctx that also ends earlier in ctx; the latest
+// such place wins; returns how many of the tokens that followed it were copied (<= r)
+static int lookup(const int32_t* ctx, int32_t ctx_len, int32_t max_ngram, int32_t r, int32_t* out) {
+  if (r <= 0) return 0;
+  int n_hi = max_ngram < ctx_len - 1 ? max_ngram : ctx_len - 1;
+  for (int n = n_hi; n >= 1; --n) {
+    const int32_t* suffix = ctx + ctx_len - n;
+    for (int end = ctx_len - 1; end >= n; --end) {  // candidate occupies [end-n, end)
+      const int32_t* cand = ctx + end - n;
+      int j = n - 1;
+      while (j >= 0 && cand[j] == suffix[j]) --j;
+      if (j < 0) {
+        int m = ctx_len - end < r ? ctx_len - end : r;
+        for (int i = 0; i < m; ++i) out[i] = ctx[end + i];
+        return m;
+      }
+    }
+  }
+  return 0;
+}
+
+static bool template_ok(const int32_t* parent, int n, int r) {
+  if (n < 1 || n > TRJ_N_MAX || r < 0 || r > n - 1 || parent[0] != -1) return false;
+  for (int i = 1; i < n; ++i)
+    if (parent[i] < 0 || parent[i] >= i) return false;
+  for (int j = 0; j < r; ++j)
+    if (parent[n - r + j] != (j == 0 ? 0 : n - r + j - 1)) return false;
+  return true;
+}
+
+// Children in index order as a CSR list; sibling rank of every node.
+struct Template {
+  int n;
+  int32_t first[TRJ_N_MAX + 1], kids[TRJ_N_MAX], rank[TRJ_N_MAX];
+  void build(const int32_t* parent, int n_nodes) {
+    n = n_nodes;
+    int cnt[TRJ_N_MAX] = {0};
+    for (int i = 1; i < n; ++i) cnt[parent[i]]++;
+    first[0] = 0;
+    for (int i = 0; i < n; ++i) first[i + 1] = first[i] + cnt[i];
+    int fill[TRJ_N_MAX] = {0};
+    rank[0] = 0;
+    for (int i = 1; i < n; ++i) {
+      int p = parent[i];
+      rank[i] = fill[p];
+      kids[first[p] + fill[p]++] = i;
+    }
+  }
+  int n_kids(int u) const { return first[u + 1] - first[u]; }
+};
+
+static void fill_tree(const int32_t* parent, const Template& t, int r, const int32_t* ctx,
+                      int32_t ctx_len, int max_ngram, uint64_t seed, int step,
+                      const int32_t* argmax, int best, int32_t* tok) {
+  const int n = t.n;
+  int32_t over[TRJ_N_MAX];  // old node under each new node, -1: none
+  over[0] = argmax ? best : -1;
+  tok[0] = ctx[ctx_len - 1];
+  for (int v = 1; v < n; ++v) {
+    int u = over[parent[v]];
+    over[v] = (u >= 0 && t.rank[v] < t.n_kids(u)) ? t.kids[t.first[u] + t.rank[v]] : -1;
+    tok[v] = over[v] >= 0 ? argmax[over[v]] : noise_token(ctx, ctx_len, seed, step, v);
+  }
+  lookup(ctx, ctx_len, max_ngram, r, tok + (n - r));
+}
+
+// device-side integer blocks of the loop
+struct LoopIn {   // host -> device every round
+  int32_t tok[TRJ_N_MAX];
+  int32_t prefix_len;
+  int32_t pad[3];
+};
+struct LoopOut {  // device -> host every round
+  int32_t argmax[TRJ_N_MAX];
+  int32_t path[TRJ_N_MAX];
+  int32_t accept_len, best, bonus, new_len, status;
+  int32_t pad[3];
+};
+struct LoopConst {  // host -> device once per tree shape
+  int32_t parent[TRJ_N_MAX];
+  int32_t node_off[2];
+  int32_t kv_off;
+  int32_t pad;
+};
+
+static int round_up(int x, int m) { return (x + m - 1) / m * m; }
+// slot bound handed to the step for a sequence of `slots` slots: coarse, so that the
+// launch shapes (and the workspace they need) take few distinct values
+static int slot_bound(int slots, int s_pool) {
+  int b = round_up(slots, 256);
+  return b < s_pool ? b : s_pool;
+}
+
+static size_t loop_fixed_bytes() {
+  return align_up(sizeof(LoopIn), 256) + align_up(sizeof(LoopOut), 256) +
+         2 * align_up(sizeof(LoopConst), 256);
+}
+
+}  // namespace trj
+
+using namespace trj;
+
+extern "C" {
+
+uint64_t trj_splitmix64(uint64_t seed, uint64_t k) { return splitmix64_at(seed, k); }
+
+int32_t trj_ahead_noise(const int32_t* h_ctx, int32_t ctx_len, uint64_t seed, int32_t step,
+                        int32_t node, int32_t* h_token) {
+  if (!h_ctx || !h_token) return TRJ_ERR_NULLPTR;
+  if (ctx_len < 1 || step < 0 || node < 0 || node >= TRJ_N_MAX) return TRJ_ERR_BAD_SHAPE;
+  *h_token = noise_token(h_ctx, ctx_len, seed, step, node);
+  return TRJ_OK;
+}
+
+int32_t trj_prompt_lookup(const int32_t* h_ctx, int32_t ctx_len, int32_t max_ngram, int32_t r,
+                          int32_t* h_out, int32_t* h_found) {
+  if (!h_ctx || !h_found || (r > 0 && !h_out)) return TRJ_ERR_NULLPTR;
+  if (ctx_len < 1 || max_ngram < 1 || r < 0) return TRJ_ERR_BAD_SHAPE;
+  *h_found = lookup(h_ctx, ctx_len, max_ngram, r, h_out);
+  return TRJ_OK;
+}
+
+int32_t trj_fill_tree(const int32_t* h_parent, int32_t n_nodes, int32_t retrieval_len,
+                      const int32_t* h_ctx, int32_t ctx_len, int32_t max_ngram, uint64_t seed,
+                      int32_t step, const int32_t* h_argmax, int32_t best, int32_t* h_tok) {
+  if (!h_parent || !h_ctx || !h_tok) return TRJ_ERR_NULLPTR;
+  if (n_nodes < 1 || n_nodes > TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  if (!template_ok(h_parent, n_nodes, retrieval_len) || ctx_len < 1 || max_ngram < 1 || step < 0 ||
+      (h_argmax && (best < 0 || best >= n_nodes)))
+    return TRJ_ERR_BAD_SHAPE;
+  Template t;
+  t.build(h_parent, n_nodes);
+  fill_tree(h_parent, t, retrieval_len, h_ctx, ctx_len, max_ngram, seed, step, h_argmax, best, h_tok);
+  return TRJ_OK;
+}
+
+int32_t tr_jacobi_generate_workspace_bytes(const trj_model_desc* desc, int32_t n_nodes,
+                                           int32_t prompt_len, int32_t max_new_tokens,
+                                           int32_t s_pool, size_t* h_bytes) {
+  if (!h_bytes) return TRJ_ERR_NULLPTR;
+  TRJ_TRY(check_model(desc));
+  if (n_nodes < 1 || n_nodes > TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  if (prompt_len < 1 || max_new_tokens < 1 || s_pool < prompt_len + max_new_tokens + n_nodes)
+    return TRJ_ERR_BAD_SHAPE;
+  size_t need = 0;
+  const int cap = prompt_len + max_new_tokens + n_nodes;
+  for (int b = 256; ; b += 256) {  // every slot bound the loop can hand to the step
+    int bound = b < s_pool ? b : s_pool;
+    size_t a = step_workspace_bytes(*desc, 1, n_nodes, bound);
+    need = a > need ? a : need;
+    for (int t : {TRJ_N_MAX, (prompt_len - 1) % TRJ_N_MAX}) {
+      if (t < 1 || t > bound) continue;
+      a = step_workspace_bytes(*desc, 1, t, bound);
+      need = a > need ? a : need;
+    }
+    if (bound >= cap || bound >= s_pool) break;
+  }
+  *h_bytes = align_up(need + loop_fixed_bytes(), 256);
+  return TRJ_OK;
+}
+
+int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
+                           void* v_pool, size_t kv_layer_stride, int32_t s_pool,
+                           const int32_t* h_prompt, int32_t prompt_len,
+                           const trj_decode_config* cfg, void* workspace, size_t ws_bytes,
+                           int32_t* h_tokens, int32_t* h_n_tokens, int32_t* h_accept_hist,
+                           int32_t* h_n_steps, void* stream) {
+  if (!cfg || !cfg->h_parent || !h_prompt || !h_tokens || !h_n_tokens || !h_n_steps || !workspace)
+    return TRJ_ERR_NULLPTR;
+  TRJ_TRY(check_model(desc));
+  const int N = cfg->n_nodes, R = cfg->retrieval_len, max_new = cfg->max_new_tokens;
+  if (N < 1 || N > TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  if (!template_ok(cfg->h_parent, N, R) || cfg->max_ngram < 1 || max_new < 1 || prompt_len < 1)
+    return TRJ_ERR_BAD_SHAPE;
+  if (s_pool < prompt_len + max_new + N || (s_pool & (TRJ_KV_BLOCK - 1))) return TRJ_ERR_BAD_SHAPE;
+  for (int i = 0; i < prompt_len; ++i)
+    if (h_prompt[i] < 0 || h_prompt[i] >= desc->vocab) return TRJ_ERR_BAD_SHAPE;
+  size_t need;
+  TRJ_TRY(tr_jacobi_generate_workspace_bytes(desc, N, prompt_len, max_new, s_pool, &need));
+  if (ws_bytes < need) return TRJ_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* base = static_cast<char*>(workspace);
+  LoopIn* d_in = reinterpret_cast<LoopIn*>(base);
+  base += align_up(sizeof(LoopIn), 256);
+  LoopOut* d_out = reinterpret_cast<LoopOut*>(base);
+  base += align_up(sizeof(LoopOut), 256);
+  LoopConst* d_tree = reinterpret_cast<LoopConst*>(base);
+  base += align_up(sizeof(LoopConst), 256);
+  LoopConst* d_chain = reinterpret_cast<LoopConst*>(base);
+  base += align_up(sizeof(LoopConst), 256);
+  void* step_ws = base;
+  const size_t step_ws_bytes = ws_bytes - loop_fixed_bytes();
+
+  LoopIn h_in{};
+  LoopOut h_out{};
+  LoopConst h_c{};
+  *h_n_tokens = 0;
+  *h_n_steps = 0;
+
+  // ---- prompt pass: the K/V of prompt[0 .. P-2] through chain-shaped trees (an ordinary
+  // causal forward), TRJ_N_MAX tokens at a time; the last prompt token becomes the root
+  int L = 0;
+  const int n_ctx0 = prompt_len - 1;
+  for (int i = 0; i < TRJ_N_MAX; ++i) h_c.parent[i] = i - 1;
+  h_c.kv_off = 0;
+  while (L < n_ctx0) {
+    const int T = n_ctx0 - L < TRJ_N_MAX ? n_ctx0 - L : TRJ_N_MAX;
+    h_c.node_off[0] = 0;
+    h_c.node_off[1] = T;
+    for (int i = 0; i < T; ++i) h_in.tok[i] = h_prompt[L + i];
+    h_in.prefix_len = L;
+    TRJ_HIP(hipMemcpyAsync(d_chain, &h_c, sizeof(h_c), hipMemcpyHostToDevice, st));
+    TRJ_HIP(hipMemcpyAsync(d_in, &h_in, sizeof(h_in), hipMemcpyHostToDevice, st));
+    TRJ_TRY(step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, d_in->tok,
+                      d_chain->parent, d_chain->node_off, &d_chain->kv_off, &d_in->prefix_len, 1, T,
+                      slot_bound(L + T, s_pool), step_ws, step_ws_bytes, nullptr, nullptr, nullptr,
+                      nullptr, nullptr, nullptr, nullptr, &d_out->status, false, st));
+    // the host blocks are reused by the next pass
+    TRJ_HIP(hipStreamSynchronize(st));
+    L += T;
+  }
+
+  // ---- decoding rounds
+  Template tmpl;
+  tmpl.build(cfg->h_parent, N);
+  for (int i = 0; i < N; ++i) h_c.parent[i] = cfg->h_parent[i];
+  h_c.node_off[0] = 0;
+  h_c.node_off[1] = N;
+  TRJ_HIP(hipMemcpyAsync(d_tree, &h_c, sizeof(h_c), hipMemcpyHostToDevice, st));
+  TRJ_HIP(hipStreamSynchronize(st));
+
+  std::vector<int32_t> ctx(h_prompt, h_prompt + prompt_len);
+  ctx.reserve(prompt_len + max_new + N);
+  int n_out = 0, step = 0;
+  bool have_pred = false, done = false;
+  while (!done) {
+    fill_tree(cfg->h_parent, tmpl, R, ctx.data(), (int)ctx.size(), cfg->max_ngram, cfg->seed, step,
+              have_pred ? h_out.argmax : nullptr, h_out.best, h_in.tok);
+    h_in.prefix_len = L;
+    TRJ_HIP(hipMemcpyAsync(d_in, &h_in, sizeof(h_in), hipMemcpyHostToDevice, st));
+    TRJ_TRY(step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, d_in->tok,
+                      d_tree->parent, d_tree->node_off, &d_tree->kv_off, &d_in->prefix_len, 1, N,
+                      slot_bound(L + N, s_pool), step_ws, step_ws_bytes, nullptr, d_out->argmax,
+                      &d_out->accept_len, &d_out->best, d_out->path, &d_out->bonus, &d_out->new_len,
+                      &d_out->status, true, st));
+    TRJ_HIP(hipMemcpyAsync(&h_out, d_out, sizeof(h_out), hipMemcpyDeviceToHost, st));
+    TRJ_HIP(hipStreamSynchronize(st));
+    if (h_out.status != 0 || h_out.accept_len < 0 || h_out.accept_len >= N) return TRJ_ERR_BAD_SHAPE;
+    have_pred = true;
+    if (h_accept_hist) h_accept_hist[step] = h_out.accept_len;
+    ++step;
+    const int a = h_out.accept_len;
+    for (int j = 1; j <= a + 1 && !done; ++j) {
+      const int32_t t = j <= a ? h_in.tok[h_out.path[j]] : h_out.bonus;
+      ctx.push_back(t);
+      h_tokens[n_out++] = t;
+      done = n_out >= max_new || t == cfg->eos_token;
+    }
+    L = h_out.new_len;
+  }
+  *h_n_tokens = n_out;
+  *h_n_steps = step;
+  return TRJ_OK;
+}
+
+}  // extern "C"

@@ -96,6 +96,18 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
                           int max_seq_slots, float scale, float* ws, int tiled, int tp,
                           uint16_t* out, hipStream_t st);
 
+// api.hip: the forward pass behind tr_verify_step (with_head == false: decoder layers
+// only, for prompt passes), its workspace need, and the model-descriptor check
+int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_pool, void* v_pool,
+              size_t kv_layer_stride, int32_t s_pool, const int32_t* tok, const int32_t* parent,
+              const int32_t* node_off, const int32_t* kv_off, const int32_t* prefix_len,
+              int32_t B, int32_t T, int32_t max_seq_slots, void* workspace, size_t ws_bytes,
+              float* logits, int32_t* argmax_out, int32_t* accept_len, int32_t* best_node,
+              int32_t* path, int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev,
+              bool with_head, hipStream_t st);
+size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_slots);
+int check_model(const trj_model_desc* m);
+
 inline int padded_rows(int T) { return T <= 32 ? 32 : (T <= 64 ? 64 : (T + 127) / 128 * 128); }
 
 }  // namespace trj

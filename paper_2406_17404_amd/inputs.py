@@ -214,6 +214,16 @@ def tree_c3(n: int, rng: np.random.Generator, chain: int = 16) -> np.ndarray:
     return p
 
 
+def tree_template(n: int, r: int, rng: np.random.Generator) -> np.ndarray:
+    """Decoding-loop template: a sparse tree of n - r nodes (tree_c1: a Jacobi chain plus
+    random branches) followed by a retrieval chain of r nodes below the root."""
+    jac = n - r
+    p = list(tree_c1(jac, rng, chain=min(8, jac)))
+    for j in range(r):
+        p.append(0 if j == 0 else len(p) - 1)
+    return np.asarray(p, np.int32)
+
+
 def gen_trees(w: Workload) -> List[np.ndarray]:
     out = []
     for s in range(len(w.prefix_len)):

@@ -203,3 +203,50 @@ def test_full_depth_7b_properties():
         assert torch.equal(rows(rb["kp"], layouts.k_index, L + 1), rows(ra["kp"], layouts.k_index, L + 8))
         assert torch.equal(rows(rb["vp"], layouts.v_index, L + 1), rows(ra["vp"], layouts.v_index, L + 8))
     say("full-depth properties hold")
+
+
+def test_full_depth_7b_decoding_loop_is_greedy_under_teacher_forcing():
+    """tr_jacobi_generate on the 32-layer model: every committed token must be the greedy
+    prediction of an ordinary causal forward over what precedes it.  That forward is one
+    chain-shaped verify step over prompt + output with logits; bf16 near ties (the tree
+    rows and the chain rows round differently) are allowed within the bf16 tolerance."""
+    say("building the 32-layer model on the device")
+    m = Full7B()
+    shape, desc = m.shape, m.desc
+    rng = np.random.default_rng(21)
+    prompt = [int(t) for t in rng.integers(0, shape.vocab, size=100)]
+    parent = I.tree_template(64, 5, rng)
+    max_new, H, dh = 24, 32, 128
+    s_pool = 256
+    stride = H * s_pool * dh
+    kp = torch.zeros(32, stride, dtype=torch.bfloat16, device=DEV)
+    vp = torch.zeros_like(kp)
+    ws = torch.empty(b.tr_jacobi_generate_workspace_bytes(desc, 64, 100, max_new, s_pool),
+                     dtype=torch.uint8, device=DEV)
+    say("generating")
+    toks, hist, steps = b.tr_jacobi_generate(desc, m.dw.struct, kp, vp, stride, s_pool, prompt, parent,
+                                             5, 3, max_new, -1, 5, ws)
+    say(f"7B loop: {len(toks)} tokens in {steps} rounds, accepted per round {hist}")
+    assert len(toks) == max_new and sum(a + 1 for a in hist) >= max_new
+    seq = prompt + toks
+    n = len(seq) - 1
+    batch = Batch([np.arange(-1, n - 1, dtype=np.int32)], [0], [np.asarray(seq[:n], np.int32)])
+    kp.zero_(), vp.zero_()
+    logits = torch.empty(n, shape.vocab, dtype=torch.float32, device=DEV)
+    o = {k: torch.zeros(c, dtype=torch.int32, device=DEV)
+         for k, c in dict(argmax=n, accept_len=1, best=1, bonus=1, new_len=1, status=1).items()}
+    path = torch.zeros((1, b.N_MAX), dtype=torch.int32, device=DEV)
+    ws2 = torch.empty(b.trj_workspace_bytes(desc, n, 1, n), dtype=torch.uint8, device=DEV)
+    b.tr_verify_step(desc, m.dw.struct, kp, vp, stride, s_pool, batch.tok, batch.parent, batch.node_off,
+                     batch.kv_off, batch.prefix, 1, n, n, ws2, logits, o["argmax"], o["accept_len"],
+                     o["best"], path, o["bonus"], o["new_len"], o["status"])
+    torch.cuda.synchronize()
+    lg = logits.cpu().numpy()
+    flips = 0
+    for i, t in enumerate(toks):
+        row = lg[len(prompt) - 1 + i]
+        if int(row.argmax()) != t:
+            flips += 1
+            assert (row.max() - row[t]) <= 1e-2 * np.abs(row).max(), (i, t)
+    say(f"7B loop: {flips} near-tie differences against the chain forward")
+    assert flips <= 2
