@@ -7,7 +7,7 @@ one batch of synthetic input of the LLaMA-7B-shaped workload: bf16, 32 layers, d
 inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1|C3]
-                    [--no-cpu-baseline] [--no-kernel-times]
+                    [--no-cpu-baseline] [--no-kernel-times] [--no-extras]
 """
 from __future__ import annotations
 
@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--workload", default="C1", choices=["C1", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-times", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the chain-length sweep and the decoding-loop leg")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="launch-shape knob for experiments (see trj_set_tunable)")
     args = ap.parse_args()
@@ -157,7 +159,8 @@ def main():
     trees = I.gen_trees(wl)
     tok_h = np.concatenate([I.gen_tokens(shape.vocab, N, wl.seed, "tree", s) if B > 1 else
                             I.gen_tokens(shape.vocab, N, wl.seed, "tree") for s in range(B)])
-    kv_off_h, s_pool = I.pool_offsets(wl.prefix_len, [N] * B)
+    # one sequence: room for the 128-row end of the chain-length sweep
+    kv_off_h, s_pool = I.pool_offsets(wl.prefix_len, [max(N, 128) if B == 1 else N] * B)
     dev = "cuda"
     i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(dev)
     parent, tok = i32(np.concatenate(trees)), i32(tok_h)
@@ -234,6 +237,62 @@ def main():
                 "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
                 "avg_launch_us": kd["avg_us"], "alg_bytes_per_launch": kd["alg_bytes"]}
 
+    # ---- one sequence only: cost of the step against the number of tree rows (a chain of
+    # n nodes is plain Jacobi decoding with n - 1 drafts, n = 1 is autoregressive decoding),
+    # and the decoding loop around the step
+    sweep, loop = None, None
+    if B == 1 and not args.no_extras:
+        sweep = []
+        for n in (1, 8, 16, 32, 64, 128):
+            par_n, tok_n = i32(np.arange(-1, n - 1)), i32(tok_h[:1].repeat(n))
+            off_n = i32([0, n])
+            ws_n = torch.empty(b.trj_workspace_bytes(desc, n, 1, L + n), dtype=torch.uint8, device=dev)
+            run = lambda: b.tr_verify_step(desc, dw.struct, k_pool, v_pool, stride, s_pool, tok_n, par_n,
+                                           off_n, kv_off, prefix, 1, n, L + n, ws_n, None, outs["argmax"],
+                                           outs["accept_len"], outs["best"], path, outs["bonus"],
+                                           outs["new_len"], outs["status"])
+            if L + n > s_pool:
+                continue
+            for _ in range(2):
+                run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                run()
+            torch.cuda.synchronize()
+            sweep.append({"chain_nodes": n, "ms_per_step": round((time.perf_counter() - t0) * 100, 4)})
+        ar = sweep[0]["ms_per_step"]
+        for e in sweep:
+            e["cost_vs_autoregressive"] = round(e["ms_per_step"] / ar, 3)
+
+        n_new, r_len = 48, 5
+        rng = np.random.default_rng(wl.seed)
+        prompt = [int(t) for t in rng.integers(0, shape.vocab, size=L + 1)]
+        tmpl = I.tree_template(N, r_len, rng)
+        sp = (L + 1 + n_new + N + 31) // 32 * 32
+        kp2 = torch.zeros(nl, H * sp * dh, device=dev, dtype=torch.bfloat16)
+        vp2 = torch.zeros_like(kp2)
+
+        def gen(max_new):
+            wsl = torch.empty(b.tr_jacobi_generate_workspace_bytes(desc, N, L + 1, max_new, sp),
+                              dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res = b.tr_jacobi_generate(desc, dw.struct, kp2, vp2, H * sp * dh, sp, prompt, tmpl, r_len, 3,
+                                       max_new, -1, wl.seed, wsl)
+            return res, time.perf_counter() - t0
+
+        gen(1)
+        (_, _, s1), t_first = gen(1)
+        (toks, hist, rounds), t_all = gen(n_new)
+        loop = {"prompt_tokens": L + 1, "tree_nodes": N, "retrieval_len": r_len, "new_tokens": len(toks),
+                "rounds": rounds, "mean_accepted_tokens_per_round": round(len(toks) / rounds, 3),
+                "prompt_pass_plus_first_round_ms": round(t_first * 1e3, 2),
+                "ms_per_round": round((t_all - t_first) * 1e3 / max(rounds - s1, 1), 4),
+                "new_tokens_per_s": round(len(toks) / t_all, 1),
+                "note": "random-init weights: drafts are accepted as rarely as an untrained model's; "
+                        "the round time is the figure of interest (step + one host exchange)"}
+
     cpu = None
     if not args.no_cpu_baseline and B == 1:  # the oracle handles one sequence at a time
         cpu = cpu_baseline(wl)
@@ -255,6 +314,7 @@ def main():
                                           + nl * sum(attn_bytes(l, N, H, dh) for l in wl.prefix_len))
                                          / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
         "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+        "chain_length_sweep": sweep, "decode_loop": loop,
     }
     print(json.dumps(out))
 
