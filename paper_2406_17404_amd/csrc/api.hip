@@ -74,7 +74,7 @@ static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int ma
   if (dtype == TRJ_BF16) {
     int ntw, qg, bpwg, ns;
     attn_bf16_plan(B, T, H, max_seq_slots, &ntw, &qg, &bpwg, &ns);
-    w->attn = c.take<float>(attn_bf16_ws_floats(T, H, dh, ns));
+    w->attn = c.take<float>(attn_bf16_ws_floats(B, qg * ntw, H, dh, ns));
   }
 }
 

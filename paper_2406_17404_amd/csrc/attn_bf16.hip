@@ -36,9 +36,13 @@ struct AttnArgs {
   const int32_t* status_dev;
   int n_heads, s_pool, bpwg, nsplit_max, qg_max;
   float scale_log2e;
-  float* po;        // [T][H][nsplit_max][DH] un-normalised partial outputs
-  float* pm;        // [T][H][nsplit_max] running max (log2 domain)
-  float* pl;        // [T][H][nsplit_max] sum of weights
+  // un-normalised partials, one per (sequence, query tile, head, split), stored as the
+  // image of the wavefront's accumulator registers: element (mt*16 + v)*64 + lane, so that
+  // every store and every load of the merge kernel is a contiguous 256-byte row
+  float* po;        // [B*tiles_per_seq][H][nsplit_max][DH/32 * 16 * 64]
+  float* pm;        // [B*tiles_per_seq][H][nsplit_max][32] running max (log2 domain)
+  float* pl;        // [B*tiles_per_seq][H][nsplit_max][32] sum of weights
+  int tiles_per_seq;
   uint16_t* out;
   int tiled, tp;
 };
@@ -79,18 +83,19 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   const int qi = (qg * NTW + nt) * 32 + n32;
   const bool valid = qi < n;
   const int qrow = valid ? r0 + qi : -1;
+  // rows past the tree's end read the last row instead (never stored, always finite):
+  // every load of the prologue is unconditional, so that the query, the ancestor bits and
+  // the first K/V block are all in flight together
+  const int qc = min(qi, n - 1);
   bf16x8 qreg[KSTEPS];
   {
-    const uint16_t* qp = a.q + ((size_t)(r0 + (valid ? qi : 0)) * a.n_heads + head) * DH + hh * 8;
+    const uint16_t* qp = a.q + ((size_t)(r0 + qc) * a.n_heads + head) * DH + hh * 8;
 #pragma unroll
-    for (int k = 0; k < KSTEPS; ++k) {
-      u32x4 v = {0, 0, 0, 0};
-      if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * k);
-      qreg[k] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int k = 0; k < KSTEPS; ++k)
+      qreg[k] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * k));
   }
-  const uint64_t anc0 = valid ? a.anc[2 * (size_t)(r0 + qi)] : 0;
-  const uint64_t anc1 = valid ? a.anc[2 * (size_t)(r0 + qi) + 1] : 0;
+  uint64_t anc0 = a.anc[2 * (size_t)(r0 + qc)];
+  uint64_t anc1 = a.anc[2 * (size_t)(r0 + qc) + 1];
 
   f32x16 o[MTV];
 #pragma unroll
@@ -122,6 +127,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
     load_k(b);
     load_v(b);
   }
+  if (!valid) anc0 = anc1 = 0;  // a row that does not exist sees no tree node
   for (; b < b1; b += KS) {
     const int key0 = b * 32;
     const bool need_mask = key0 + 32 > L;
@@ -251,54 +257,55 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
     return;
   }
 
-  // ---- un-normalised partial of this workgroup (merged by attn_combine_kernel)
-  if (ks == 0 && qrow >= 0) {
-    size_t pidx = ((size_t)qrow * a.n_heads + head) * a.nsplit_max + sp;
+  // ---- un-normalised partial of this workgroup (merged by attn_combine_kernel): the
+  // whole register tile, rows that do not exist included (finite, never read back)
+  if (ks == 0) {
+    const size_t pidx =
+        (((size_t)s * a.tiles_per_seq + qg * NTW + nt) * a.n_heads + head) * a.nsplit_max + sp;
     if (hh == 0) {
-      a.pm[pidx] = mg;
-      a.pl[pidx] = lg;
+      a.pm[pidx * 32 + n32] = mg;
+      a.pl[pidx * 32 + n32] = lg;
     }
-    float* orow = a.po + pidx * DH;
+    float* img = a.po + pidx * OW + lane;
 #pragma unroll
     for (int mt = 0; mt < MTV; ++mt)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 v = {o[mt][4 * g], o[mt][4 * g + 1], o[mt][4 * g + 2], o[mt][4 * g + 3]};
-        *reinterpret_cast<f32x4*>(orow + 32 * mt + 8 * g + 4 * hh) = v;
-      }
+      for (int v = 0; v < 16; ++v) img[(mt * 16 + v) * 64] = o[mt][v];
   }
 }
 
-// Merge the partials of every (row, head) in split order; one thread per 8 columns.  The
-// loads of a batch of splits are all issued together (clamped, never predicated).
+// Merge the partials of one (sequence, query tile, head) in split order.  512 threads: the
+// thread (lane, mt, half) owns the 8 accumulator registers v = 8*half .. 8*half+7 of tile mt
+// that lane `lane` of the attention wavefront held, i.e. query lane%32, 8 columns.  The loads
+// of a batch of splits are all issued together (clamped, never predicated).
 template <int DH>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, const int32_t* row_seq,
-                                                           int T) {
-  constexpr int CB = 8;
-  const int t = blockIdx.x;
-  const int gcol = blockIdx.y * 256 + threadIdx.x;
-  if (gcol * 8 >= a.n_heads * DH) return;
-  const int head = gcol * 8 / DH, c = gcol * 8 % DH;
-  const int s = row_seq[t];
-  if (s < 0 || a.status_dev[s] != 0) return;  // rows of malformed sequences stay zero
-  const int n = a.node_off[s + 1] - a.node_off[s];
+__global__ __launch_bounds__(512) void attn_combine_kernel(AttnArgs a) {
+  constexpr int CB = 8, MTV = DH / 32, OW = MTV * 16 * 64;
+  const int tile = blockIdx.x % a.tiles_per_seq, s = blockIdx.x / a.tiles_per_seq;
+  const int head = blockIdx.y;
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int mt = grp >> 1, v0 = (grp & 1) * 8;
+  if (mt >= MTV) return;
+  if (a.status_dev[s] != 0) return;  // rows of malformed sequences stay zero
+  const int r0 = a.node_off[s], n = a.node_off[s + 1] - r0;
+  if (tile * 32 >= n) return;
   const int nb = (a.prefix_len[s] + n + 31) >> 5;
   const int nsplit = (nb + a.bpwg - 1) / a.bpwg;
   if (nsplit == 1) return;  // written by the attention kernel itself
-  const size_t base = ((size_t)t * a.n_heads + head) * a.nsplit_max;
+  const int n32 = lane & 31, hh = lane >> 5;
+  const size_t base = (((size_t)s * a.tiles_per_seq + tile) * a.n_heads + head) * a.nsplit_max;
   float mrun = NEG_BIG, lrun = 0.f;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int k0 = 0; k0 < nsplit; k0 += CB) {
-    float ms[CB], ls[CB];
-    f32x4 x0[CB], x1[CB];
+    float ms[CB], ls[CB], x[CB][8];
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
       const int k = min(k0 + j, nsplit - 1);
-      ms[j] = a.pm[base + k];
-      ls[j] = a.pl[base + k];
-      const float* pr = a.po + (base + k) * DH + c;
-      x0[j] = *reinterpret_cast<const f32x4*>(pr);
-      x1[j] = *reinterpret_cast<const f32x4*>(pr + 4);
+      ms[j] = a.pm[(base + k) * 32 + n32];
+      ls[j] = a.pl[(base + k) * 32 + n32];
+      const float* img = a.po + (base + k) * OW + (mt * 16 + v0) * 64 + lane;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[j][e] = img[e * 64];
     }
     float mb = mrun;
 #pragma unroll
@@ -312,16 +319,19 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, const int
       const float wgt = k0 + j < nsplit ? exp2f(ms[j] - mb) : 0.f;
       lrun += wgt * ls[j];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[e] += wgt * x0[j][e];
-        acc[4 + e] += wgt * x1[j][e];
-      }
+      for (int e = 0; e < 8; ++e) acc[e] += wgt * x[j][e];
     }
     mrun = mb;
   }
+  const int qi = tile * 32 + n32;
+  if (qi >= n) return;
   const float inv = 1.0f / lrun;
-  attn_store_row<DH>(a, t, head, c, u32x2{pack2bf(acc[0] * inv, acc[1] * inv), pack2bf(acc[2] * inv, acc[3] * inv)});
-  attn_store_row<DH>(a, t, head, c + 4, u32x2{pack2bf(acc[4] * inv, acc[5] * inv), pack2bf(acc[6] * inv, acc[7] * inv)});
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    u32x2 v = {pack2bf(acc[4 * g] * inv, acc[4 * g + 1] * inv),
+               pack2bf(acc[4 * g + 2] * inv, acc[4 * g + 3] * inv)};
+    attn_store_row<DH>(a, r0 + qi, head, 32 * mt + 8 * ((v0 >> 2) + g) + 4 * hh, v);
+  }
 }
 
 // zero fill (rows of malformed sequences and the padding rows of the tiled output)
@@ -353,9 +363,10 @@ void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int*
   *nsplit_max = (nb + b - 1) / b;
 }
 
-size_t attn_bf16_ws_floats(int T, int n_heads, int dh, int nsplit_max) {
+size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int nsplit_max) {
   // partials: none needed when every sequence fits one workgroup
-  return nsplit_max > 1 ? (size_t)T * n_heads * nsplit_max * (dh + 2) : 64;
+  return nsplit_max > 1 ? (size_t)B * tiles_per_seq * n_heads * nsplit_max * (dh / 32 * 1024 + 64)
+                        : 64;
 }
 
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
@@ -367,12 +378,13 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   if (dh != 64 && dh != 128) return TRJ_ERR_BAD_SHAPE;
   int ntw, qg_max, bpwg, nsplit_max;
   attn_bf16_plan(B, T, n_heads, max_seq_slots, &ntw, &qg_max, &bpwg, &nsplit_max);
-  size_t rows = nsplit_max > 1 ? (size_t)T * n_heads * nsplit_max : 0;
+  const int tiles_per_seq = qg_max * ntw;
+  size_t parts = nsplit_max > 1 ? (size_t)B * tiles_per_seq * n_heads * nsplit_max : 0;
   float* po = ws;
-  float* pm = ws + rows * dh;
-  float* pl = pm + rows;
+  float* pm = ws + parts * (dh / 32 * 1024);
+  float* pl = pm + parts * 32;
   AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, s_pool,
-             bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, out, tiled, tp};
+             bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
   dim3 grid(nsplit_max * qg_max, n_heads, B);
   const int ks = ATTN_WAVES / ntw;
   size_t lds = (size_t)(ks / 2) * ntw * (dh / 32) * 16 * 64 * sizeof(float);
@@ -395,9 +407,9 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   int rc = check_launch();
   if (rc || nsplit_max == 1) return rc;
   ProfScope ps_(KC_ATTN_COMBINE, st);
-  dim3 cgrid(T, (n_heads * dh / 8 + 255) / 256);
-  if (dh == 128) attn_combine_kernel<128><<<cgrid, 256, 0, st>>>(a, row_seq, T);
-  else attn_combine_kernel<64><<<cgrid, 256, 0, st>>>(a, row_seq, T);
+  dim3 cgrid(B * tiles_per_seq, n_heads);
+  if (dh == 128) attn_combine_kernel<128><<<cgrid, 512, 0, st>>>(a);
+  else attn_combine_kernel<64><<<cgrid, 512, 0, st>>>(a);
   return check_launch();
 }
 

@@ -296,9 +296,9 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   int pps = (nph + split_k - 1) / split_k;
   g.split_k = (nph + pps - 1) / pps;  // never an empty split
   int ntiles = n_out >> 5, tblocks = tp / (32 * g.mt);
-  int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2)
+  int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt == 4 ? 3 : 2);
-  g.rt = shape == 1 ? 4 : 2;
+  g.rt = (shape == 1 || shape == 4) ? 4 : 2;
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : 2);
   return g;
 }
@@ -311,7 +311,8 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
   if (tp % (32 * g.mt) != 0) return TRJ_ERR_BAD_SHAPE;
 #define TRJ_P(M)                                                                             \
   do {                                                                                       \
-    if (g.rt == 4) launch_p<M, 4, 1, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);       \
+    if (g.rt == 4 && g.kw == 2) launch_p<M, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st); \
+    else if (g.rt == 4) launch_p<M, 4, 1, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);       \
     else if (g.kw == 4) launch_p<M, 2, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);  \
     else launch_p<M, 2, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);                 \
   } while (0)

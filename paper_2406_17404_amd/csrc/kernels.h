@@ -9,7 +9,7 @@ struct Tunables {
   int gemm_target_wgs = 256;   // split-k is raised until a GEMM has this many workgroups
   int max_split_k = 8;
   int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..3 force one
-  int attn_target_wgs = 1024;  // upper bound on attention workgroups per launch
+  int attn_target_wgs = 256;   // attention workgroups per launch aimed at (one per CU)
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
 extern Tunables g_tune;
@@ -87,7 +87,7 @@ int launch_tile_activation(const uint16_t* x, int T, int n, int tp, uint16_t* xp
 // attn_bf16.hip
 void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int* qg_max, int* bpwg,
                     int* nsplit_max);
-size_t attn_bf16_ws_floats(int T, int n_heads, int dh, int nsplit_max);
+size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int nsplit_max);
 int launch_zero_bytes(void* p, size_t bytes, hipStream_t st);
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
                           const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
