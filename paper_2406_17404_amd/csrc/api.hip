@@ -298,7 +298,7 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
     // rows of malformed sequences read as zeros
     TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
-                                 (const uint16_t*)v_layer, w.anc, w.row_seq, node_off, kv_off, prefix_len,
+                                 (const uint16_t*)v_layer, w.anc, node_off, kv_off, prefix_len,
                                  w.status, B, T, n_heads, head_dim, s_pool, max_seq_slots, scale,
                                  w.attn, 0, 0, (uint16_t*)out, st);
   }
@@ -420,7 +420,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
       { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
                               w.t.row_slot, w.q, kl, vl, st)); }
-      TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off, prefix_len, status_dev,
+      TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, node_off, kv_off, prefix_len, status_dev,
                                     B, T, H, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
                                     w.op, st));
       { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }

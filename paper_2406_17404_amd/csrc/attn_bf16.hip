@@ -25,6 +25,9 @@
 
 namespace trj {
 
+constexpr float NEG_BIG = -1e30f;
+constexpr int ATTN_WAVES = 8;
+
 struct AttnArgs {
   const uint16_t* q;
   const uint16_t* k_layer;
@@ -47,8 +50,85 @@ struct AttnArgs {
   int tiled, tp;
 };
 
-constexpr float NEG_BIG = -1e30f;
-constexpr int ATTN_WAVES = 8;
+
+// Online-softmax update of one query tile with one block of 32 keys: S^T accumulators in,
+// packed bf16 probabilities out (the B operand of the second product), running max m and
+// sum l of this lane's query updated, `alpha` = factor for the O accumulators.
+//
+// Blocks that lie wholly in the prefix (all but the last few of a sequence) take this
+// lean form: no visibility tests; the max works on the raw scores and the scale
+// (log2 e / sqrt(dh), > 0) goes into one fused multiply-add per key; v_exp_f32 directly
+// (results below the normal range flush to zero, as they should).
+__device__ inline void softmax_tile_prefix(const f32x16& sacc, float scale, float& m, float& l,
+                                           float& alpha, u32x4 (&pk)[2]) {
+  float mx = sacc[0];
+#pragma unroll
+  for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx * scale);
+  alpha = __builtin_amdgcn_exp2f(m - m_new);
+  float lsum = 0.f;
+  float p[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], scale, -m_new));
+    lsum += p[v];
+  }
+  l = l * alpha + lsum;
+  m = m_new;
+#pragma unroll
+  for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk[kg][e] = pack2bf(p[8 * kg + 2 * e], p[8 * kg + 2 * e + 1]);
+}
+
+// Blocks that overlap the tree's own slots (at most 5 per sequence): ancestor bits decide
+// which keys a query sees; a key that is not visible contributes exactly 0, also while
+// nothing is visible yet (m == NEG_BIG).
+__device__ inline void softmax_tile_tree(const f32x16& sacc, int key0, int hh, int L, uint64_t anc0,
+                                         uint64_t anc1, float scale, float& m, float& l,
+                                         float& alpha, u32x4 (&pk)[2]) {
+  float sv[16];
+  float mx = NEG_BIG;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    bool vis = true;
+    const int kk = key0 + 8 * (v >> 2) + 4 * hh + (v & 3);
+    if (kk >= L) {
+      const int j = kk - L;
+      vis = j < 64 ? ((anc0 >> j) & 1) : (j < 128 ? ((anc1 >> (j - 64)) & 1) : 0);
+    }
+    sv[v] = vis ? sacc[v] * scale : NEG_BIG;
+    mx = fmaxf(mx, sv[v]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  alpha = exp2f(m - m_new);
+  float lsum = 0.f;
+  float p[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    p[v] = sv[v] > -1e29f ? exp2f(sv[v] - m_new) : 0.f;
+    lsum += p[v];
+  }
+  l = l * alpha + lsum;
+  m = m_new;
+#pragma unroll
+  for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk[kg][e] = pack2bf(p[8 * kg + 2 * e], p[8 * kg + 2 * e + 1]);
+}
+
+// O accumulators times alpha; skipped when no query of the wavefront moved its maximum
+// (alpha == 1 in every lane), which is the common case once a few blocks have been seen
+template <int MTV>
+__device__ inline void rescale_o(f32x16 (&o)[MTV], float alpha) {
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) == 0) return;
+#pragma unroll
+  for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[mt][v] *= alpha;
+}
 
 template <int DH>
 __device__ inline void attn_store_row(const AttnArgs& a, int t, int head, int c, u32x2 v) {
@@ -156,48 +236,18 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
           }
         }
     }
-    float sv[16];
-    float mx = NEG_BIG;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      bool vis = true;
-      if (need_mask) {
-        int kk = key0 + 8 * (v >> 2) + 4 * hh + (v & 3);
-        if (kk >= L) {
-          int j = kk - L;
-          vis = j < 64 ? ((anc0 >> j) & 1) : (j < 128 ? ((anc1 >> (j - 64)) & 1) : 0);
-        }
-      }
-      sv[v] = vis ? sacc[v] * a.scale_log2e : NEG_BIG;
-      mx = fmaxf(mx, sv[v]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = exp2f(m - m_new);
-    float lsum = 0.f;
-    float p[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      p[v] = sv[v] > -1e29f ? exp2f(sv[v] - m_new) : 0.f;
-      lsum += p[v];
-    }
-    l = l * alpha + lsum;
-    m = m_new;
+    float alpha;
     u32x4 pk[2];
+    if (need_mask) softmax_tile_tree(sacc, key0, hh, L, anc0, anc1, a.scale_log2e, m, l, alpha, pk);
+    else softmax_tile_prefix(sacc, a.scale_log2e, m, l, alpha, pk);
+    rescale_o<MTV>(o, alpha);
 #pragma unroll
-    for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pk[kg][e] = pack2bf(p[8 * kg + 2 * e], p[8 * kg + 2 * e + 1]);
-#pragma unroll
-    for (int mt = 0; mt < MTV; ++mt) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[mt][v] *= alpha;
+    for (int mt = 0; mt < MTV; ++mt)
 #pragma unroll
       for (int kg = 0; kg < 2; ++kg)
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[mt][kg]),
                                                         __builtin_bit_cast(bf16x8, pk[kg]), o[mt],
                                                         0, 0, 0);
-    }
     if (bn < b1) load_v(bn);  // in flight during the next S^T and softmax
   }
 
@@ -273,6 +323,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
       for (int v = 0; v < 16; ++v) img[(mt * 16 + v) * 64] = o[mt][v];
   }
 }
+
 
 // Merge the partials of one (sequence, query tile, head) in split order.  512 threads: the
 // thread (lane, mt, half) owns the 8 accumulator registers v = 8*half .. 8*half+7 of tile mt
@@ -370,7 +421,7 @@ size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int ns
 }
 
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
-                          const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
+                          const uint64_t* anc, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,
                           const int32_t* status_dev, int B, int T, int n_heads, int dh, int s_pool,
                           int max_seq_slots, float scale, float* ws, int tiled, int tp,

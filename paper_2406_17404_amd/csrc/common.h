@@ -34,7 +34,6 @@ __host__ __device__ inline float bf2f(uint16_t b) {
 __device__ inline uint32_t pack2bf(float lo, float hi) {
   return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
 }
-
 // ---- element-offset functions of the tiled layouts (see include/trjacobi.h)
 // weight tile layout: packed row r, column k, n_in columns
 __host__ __device__ inline size_t w_off(int r, int k, int n_in) {

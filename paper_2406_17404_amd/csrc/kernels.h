@@ -90,7 +90,7 @@ void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int*
 size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int nsplit_max);
 int launch_zero_bytes(void* p, size_t bytes, hipStream_t st);
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
-                          const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
+                          const uint64_t* anc, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,
                           const int32_t* status_dev, int B, int T, int n_heads, int dh, int s_pool,
                           int max_seq_slots, float scale, float* ws, int tiled, int tp,

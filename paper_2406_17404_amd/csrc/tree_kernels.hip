@@ -72,19 +72,27 @@ __global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
   }
 }
 
+// rows that no valid sequence covers must read as "skip": one launch clears all five arrays
+__global__ void prep_clear_kernel(int32_t* depth, int32_t* anc_words, int32_t* row_slot,
+                                  int32_t* row_pos, int32_t* row_seq, int T) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < 4 * T) anc_words[i] = 0;
+  if (i < T) {
+    depth[i] = 0;
+    if (row_slot) {
+      row_slot[i] = -1;
+      row_pos[i] = 0;
+      row_seq[i] = -1;
+    }
+  }
+}
+
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                      const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
                      int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
                      int32_t* row_seq, hipStream_t st) {
-  // rows that no valid sequence covers must read as "skip"
-  int nb = (T + 255) / 256;
-  fill_i32_kernel<<<nb, 256, 0, st>>>(depth, 0, T);
-  fill_i32_kernel<<<(4 * T + 255) / 256, 256, 0, st>>>(reinterpret_cast<int32_t*>(anc), 0, 4 * T);
-  if (row_slot) {
-    fill_i32_kernel<<<nb, 256, 0, st>>>(row_slot, -1, T);
-    fill_i32_kernel<<<nb, 256, 0, st>>>(row_pos, 0, T);
-    fill_i32_kernel<<<nb, 256, 0, st>>>(row_seq, -1, T);
-  }
+  prep_clear_kernel<<<(4 * T + 255) / 256, 256, 0, st>>>(depth, reinterpret_cast<int32_t*>(anc),
+                                                         row_slot, row_pos, row_seq, T);
   tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool,
                                             max_seq_slots, depth, anc, status_dev, row_slot, row_pos, row_seq);
   return check_launch();

@@ -88,6 +88,32 @@ def test_packed_ragged_batch(dtype):
         assert rel_err(g, O.tree_attention(*c)) <= TOL[dtype]
 
 
+def test_packed_ragged_batch_repeated_with_cold_caches():
+    """The same ragged batch many times, every third launch after a 256 MiB write that
+    empties the caches: launches that find their data in HBM run with a different timing
+    between the wavefronts of a workgroup, and every one of them must give the same rows
+    (a masked tree block once came out with one extra visible key in a few percent of
+    such launches)."""
+    H, dh = 4, 128
+    rng = np.random.default_rng(5)
+    cases = []
+    for s in range(6):
+        L, n = int(rng.integers(0, 700)), int(rng.integers(1, 129))
+        cases.append(case(100 + s, H, dh, L, n, "bf16"))
+    want = [O.tree_attention(*c) for c in cases]
+    first = None
+    for trial in range(45):
+        if trial % 3 == 0:
+            torch.randn(64 * 1024 * 1024, device=DEV)
+        got = run_attention("bf16", H, dh, cases, align=32)
+        for g, w in zip(got, want):
+            assert rel_err(g, w) <= TOL["bf16"], trial
+        if first is None:
+            first = got
+        else:
+            assert all(np.array_equal(a, c) for a, c in zip(first, got)), trial
+
+
 def test_bf16_launch_shapes_give_the_same_answer():
     """Different splits of the key range only change fp32 summation order."""
     H, dh, L, n = 4, 128, 1500, 64
@@ -100,7 +126,7 @@ def test_bf16_launch_shapes_give_the_same_answer():
             got = run_attention("bf16", H, dh, [c])[0]
             assert rel_err(got, want) <= 1e-2
     finally:
-        b.trj_set_tunable("attn_target_wgs", 1024)
+        b.trj_set_tunable("attn_target_wgs", 256)
         b.trj_set_tunable("attn_min_bpw", 2)
 
 
