@@ -293,6 +293,43 @@ def main():
                 "note": "random-init weights: drafts are accepted as rarely as an untrained model's; "
                         "the round time is the figure of interest (step + one host exchange)"}
 
+    # ---- the standalone tree-attention entry point at the sweep sizes (prefix 2k..32k, 64-node
+    # random trees, 32 heads x 128), layers rotated so that no launch finds its K/V in a cache
+    attn_sweep = None
+    if B == 1 and not args.no_extras:
+        attn_sweep = []
+        for Ls, Ns in ((2048, 64), (8192, 64), (8192, 128), (32768, 64)):
+            sp = (Ls + Ns + 63) // 64 * 64
+            n_rot = max(4, min(16, int(3e9 // (2 * H * sp * dh * 2))))
+            qd = torch.randn(Ns, H, dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            kps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            vps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            par_s = i32(I.tree_random(Ns, np.random.default_rng(wl.seed)))
+            off_s, kvo_s, pre_s = i32([0, Ns]), i32([0]), i32([Ls])
+            ws_s = torch.empty(b.trj_workspace_bytes(desc, Ns, 1, Ls + Ns), dtype=torch.uint8, device=dev)
+            out_s = torch.empty(Ns, H, dh, device=dev, dtype=torch.bfloat16)
+
+            def run_all():
+                for l in range(n_rot):
+                    b.tree_attention(qd, kps[l], vps[l], par_s, off_s, kvo_s, pre_s, 1, Ns, H, dh, sp,
+                                     Ls + Ns, b.BF16, float(1.0 / np.sqrt(dh)), ws_s, out_s)
+            run_all()
+            torch.cuda.synchronize()
+            t_us = {}
+            for name in ("tree_attn", "attn_combine"):
+                b.trj_profile_begin(b.KERNEL_CLASSES[name], 2 * n_rot)
+                run_all()
+                torch.cuda.synchronize()
+                ts = b.trj_profile_end(2 * n_rot)
+                t_us[name] = 1e3 * sum(ts) / max(len(ts), 1)
+            by = attn_bytes(Ls, Ns, H, dh)
+            tot = t_us["tree_attn"] + t_us["attn_combine"]
+            attn_sweep.append({"prefix_len": Ls, "tree_nodes": Ns, "attn_us": round(t_us["tree_attn"], 2),
+                               "merge_us": round(t_us["attn_combine"], 2), "alg_bytes": by,
+                               "GBps": round(by / (tot * 1e-6) / 1e9, 1),
+                               "frac_hbm": round(by / (tot * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)})
+            del kps, vps
+
     cpu = None
     if not args.no_cpu_baseline and B == 1:  # the oracle handles one sequence at a time
         cpu = cpu_baseline(wl)
@@ -314,7 +351,7 @@ def main():
                                           + nl * sum(attn_bytes(l, N, H, dh) for l in wl.prefix_len))
                                          / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
         "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
-        "chain_length_sweep": sweep, "decode_loop": loop,
+        "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,
     }
     print(json.dumps(out))
 
