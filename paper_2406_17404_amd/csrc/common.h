@@ -31,8 +31,13 @@ __host__ __device__ inline float bf2f(uint16_t b) {
   c.u = ((uint32_t)b) << 16;
   return c.f;
 }
+// two fp32 -> packed bf16 pair (lo in bits 0..15) with the hardware conversion: one
+// v_cvt_pk_bf16_f32 on gfx950, round to nearest even, NaN kept quiet
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ inline uint32_t pack2bf(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 // ---- element-offset functions of the tiled layouts (see include/trjacobi.h)
 // weight tile layout: packed row r, column k, n_in columns

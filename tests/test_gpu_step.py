@@ -236,3 +236,65 @@ def test_host_side_errors():
     with pytest.raises(b.TrjError) as e:
         b.tr_verify_step(*args(t, mss=100))
     assert e.value.status == -2
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    """The step only enqueues kernels on the caller's stream (its buffers are cleared by
+    fill kernels, not by memset nodes), so it can be captured in a HIP graph; every replay
+    must equal the eager result, with eager work and synchronisation between replays."""
+    import torch
+    from gpu_util import DEV, tdtype, to_dev
+    shape = I.ModelShape(2, 512, 4, 128, 1408, 1024, "bf16")
+    w = I.gen_weights(shape, 31)
+    desc, dw = device_weights(shape, w)
+    rng = np.random.default_rng(31)
+    L, n = 300, 40
+    tree = I.tree_random(n, rng)
+    batch = Batch([tree], [L], [I.gen_tokens(shape.vocab, n, 31, "tree")])
+    stride = shape.n_heads * batch.s_pool * shape.head_dim
+    g0 = torch.Generator(device=DEV).manual_seed(3)
+    k0 = torch.randn(2, stride, device=DEV, generator=g0).to(torch.bfloat16)
+    v0 = torch.randn(2, stride, device=DEV, generator=g0).to(torch.bfloat16)
+    kp, vp = k0.clone(), v0.clone()
+    ws = torch.empty(b.trj_workspace_bytes(desc, n, 1, L + n), dtype=torch.uint8, device=DEV)
+    logits = torch.empty(n, shape.vocab, dtype=torch.float32, device=DEV)
+    o = {k: torch.zeros(c, dtype=torch.int32, device=DEV)
+         for k, c in dict(argmax=n, accept_len=1, best=1, bonus=1, new_len=1, status=1).items()}
+    path = torch.zeros((1, b.N_MAX), dtype=torch.int32, device=DEV)
+
+    def step():
+        b.tr_verify_step(desc, dw.struct, kp, vp, stride, batch.s_pool, batch.tok, batch.parent,
+                         batch.node_off, batch.kv_off, batch.prefix, 1, n, L + n, ws, logits, o["argmax"],
+                         o["accept_len"], o["best"], path, o["bonus"], o["new_len"], o["status"])
+
+    step()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in o.items()}
+    ref.update(logits=logits.clone(), path=path.clone(), kp=kp.clone(), vp=vp.clone())
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        kp.copy_(k0), vp.copy_(v0)
+        step()
+        torch.cuda.synchronize()
+        kp.copy_(k0), vp.copy_(v0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        kp.copy_(k0), vp.copy_(v0)
+        logits.fill_(float("nan"))
+        for v in o.values():
+            v.fill_(-9)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in o:
+            assert torch.equal(o[k], ref[k]), (replay, k)
+        assert torch.equal(logits, ref["logits"]) and torch.equal(path, ref["path"]), replay
+        assert torch.equal(kp, ref["kp"]) and torch.equal(vp, ref["vp"]), replay
+        kp.copy_(k0), vp.copy_(v0)
+        step()                       # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(logits, ref["logits"])
