@@ -28,7 +28,9 @@ cache or an acceptance formula); the same list is in the design notes:
   * rotary pairing (j, j + dh/2), angle pos * theta**(-2j/dh);
   * a node attends to every prefix token, its ancestors and itself;
   * ties: argmax -> lowest token id; equally long accepted paths -> lowest node index;
-  * the accepted path's K/V rows are moved to follow the prefix contiguously.
+  * the accepted path's K/V rows are moved to follow the prefix contiguously;
+  * grouped-query attention (the paper's general-domain base model shares K/V heads
+    between query heads): query head h reads K/V head h // (n_heads // n_kv_heads).
 RoPE pairing/base and the RMSNorm epsilon are conventions the paper cannot pin:
 "parity unpinned" for those two choices (any self-consistent choice passes the
 brute-force pin); they are pinned only to the stated closed forms.
@@ -120,14 +122,17 @@ def silu(z):
 def tree_attention(q, k, v, parent, prefix_len, scale=None):
     """Tree-masked attention for one sequence.
 
-    q[N, H, dh]; k, v[H, S, dh] with S >= prefix_len + N, tree node j stored at slot
-    prefix_len + j.  Node i attends to slots 0..prefix_len-1 and to prefix_len + j
-    for every j on its root path (itself included).  Returns out[N, H, dh].
+    q[N, H, dh]; k, v[Hkv, S, dh] with S >= prefix_len + N, tree node j stored at slot
+    prefix_len + j; Hkv divides H and query head h reads K/V head h // (H // Hkv)
+    (Hkv == H: ordinary multi-head attention).  Node i attends to slots
+    0..prefix_len-1 and to prefix_len + j for every j on its root path (itself
+    included).  Returns out[N, H, dh].
     """
     q = np.asarray(q, F64)
     k = np.asarray(k, F64)
     v = np.asarray(v, F64)
     n, h, dh = q.shape
+    group = h // k.shape[0]
     L = int(prefix_len)
     if scale is None:
         scale = 1.0 / np.sqrt(dh)
@@ -136,10 +141,10 @@ def tree_attention(q, k, v, parent, prefix_len, scale=None):
     for i in range(n):
         slots = np.concatenate([np.arange(L), L + np.nonzero(mask[i])[0]])
         for hh in range(h):
-            s = (k[hh, slots] @ q[i, hh]) * scale
+            s = (k[hh // group, slots] @ q[i, hh]) * scale
             p = np.exp(s - s.max())
             p /= p.sum()
-            out[i, hh] = p @ v[hh, slots]
+            out[i, hh] = p @ v[hh // group, slots]
     return out
 
 
@@ -147,10 +152,11 @@ def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=No
     """One forward pass of the decoder over the tree's token rows (one sequence).
 
     shape: object with n_layers, d_model, n_heads, head_dim, d_ffn, vocab, rms_eps,
-    rope_theta.  weights: dict with embed[V,d], g_final[d], w_lm[V,d] and layers[l] =
-    {g_attn, wqkv[3*H*dh, d] (rows Wq;Wk;Wv), wo[d, H*dh], g_ffn, w_gate_up[2F, d]
-    (rows Wg;Wu), w_down[d, F]}; y = x @ W.T everywhere.  kv[l] = (K, V), fp64 arrays
-    [H, S, dh]; slots 0..prefix_len-1 hold the prefix (K already rotated); this call
+    rope_theta and optionally n_kv_heads (0 or absent: n_heads).  weights: dict with
+    embed[V,d], g_final[d], w_lm[V,d] and layers[l] = {g_attn, wqkv[(H+2*Hkv)*dh, d]
+    (rows Wq;Wk;Wv), wo[d, H*dh], g_ffn, w_gate_up[2F, d] (rows Wg;Wu), w_down[d, F]};
+    y = x @ W.T everywhere.  kv[l] = (K, V), fp64 arrays [Hkv, S, dh]; slots
+    0..prefix_len-1 hold the prefix (K already rotated); this call
     writes the tree's K/V into slots prefix_len + i.  Returns logits[N, V] (fp64).
     `collect`, if a dict, receives per-layer intermediates for kernel-level tests.
     """
@@ -158,7 +164,8 @@ def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=No
     n = len(tok)
     L = int(prefix_len)
     H, dh, F = shape.n_heads, shape.head_dim, shape.d_ffn
-    hd = H * dh
+    Hkv = getattr(shape, "n_kv_heads", 0) or H
+    hd, kvd = H * dh, Hkv * dh
     pos = L + tree_depth(parent)
     x = np.asarray(weights["embed"], F64)[tok]  # [n, d]
     for l in range(shape.n_layers):
@@ -167,8 +174,8 @@ def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=No
         h = rmsnorm(x, w["g_attn"], shape.rms_eps)
         qkv = h @ np.asarray(w["wqkv"], F64).T
         q = rope(qkv[:, :hd].reshape(n, H, dh), pos, shape.rope_theta)
-        kk = rope(qkv[:, hd:2 * hd].reshape(n, H, dh), pos, shape.rope_theta)
-        vv = qkv[:, 2 * hd:].reshape(n, H, dh)
+        kk = rope(qkv[:, hd:hd + kvd].reshape(n, Hkv, dh), pos, shape.rope_theta)
+        vv = qkv[:, hd + kvd:].reshape(n, Hkv, dh)
         K[:, L:L + n] = kk.transpose(1, 0, 2)
         V[:, L:L + n] = vv.transpose(1, 0, 2)
         o = tree_attention(q, K, V, parent, L)

@@ -35,6 +35,11 @@ class ModelShape:
     dtype: str  # "f32" or "bf16"
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
+    n_kv_heads: int = 0  # grouped-query attention: K/V heads (0: as many as query heads)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
 
 
 @dataclass(frozen=True)
@@ -50,6 +55,8 @@ class Workload:
 TINY = ModelShape(2, 256, 4, 64, 1024, 2048, "f32")
 LLAMA7B = ModelShape(32, 4096, 32, 128, 11008, 32000, "bf16")
 CODE7B = ModelShape(32, 4096, 32, 128, 11008, 32256, "bf16")
+# 8B-class shape with grouped-query attention: 32 query heads share 8 K/V heads
+GQA8B = ModelShape(32, 4096, 32, 128, 14336, 128256, "bf16", 1e-5, 500000.0, 8)
 
 
 def workload(name: str) -> Workload:
@@ -61,6 +68,8 @@ def workload(name: str) -> Workload:
         return Workload("C1", LLAMA7B, 1001, (1024,), "c1", 64)
     if name == "C3":
         return Workload("C3", CODE7B, 1003, (4096,), "c3", 128)
+    if name == "G1":  # the 7B workload's recipe on the grouped-query 8B shape
+        return Workload("G1", GQA8B, 1005, (1024,), "c1", 64)
     if name == "C4":
         rng = _rng(1004, "prefix_len")
         lens = tuple(int(v) for v in rng.integers(256, 4097, size=16))
@@ -125,12 +134,14 @@ def _normal(rng, shape, std, dtype):
 # ----------------------------------------------------------------------------- weights
 def gen_layer_weights(s: ModelShape, seed: int, layer: int) -> Dict[str, np.ndarray]:
     """One decoder layer: every matrix i.i.d. N(0, 0.02^2), row-major [out, in];
-    norm gains 1.  wqkv rows are [Wq; Wk; Wv], w_gate_up rows are [Wg; Wu]."""
+    norm gains 1.  wqkv rows are [Wq; Wk; Wv] (Wk, Wv have kv_heads * head_dim rows),
+    w_gate_up rows are [Wg; Wu]."""
     d, f = s.d_model, s.d_ffn
     hd = s.n_heads * s.head_dim
+    kvd = s.kv_heads * s.head_dim
     return {
         "g_attn": np.ones(d, np.float32),
-        "wqkv": _normal(_rng(seed, "wqkv", layer), (3 * hd, d), 0.02, s.dtype),
+        "wqkv": _normal(_rng(seed, "wqkv", layer), (hd + 2 * kvd, d), 0.02, s.dtype),
         "wo": _normal(_rng(seed, "wo", layer), (d, hd), 0.02, s.dtype),
         "g_ffn": np.ones(d, np.float32),
         "w_gate_up": _normal(_rng(seed, "wgu", layer), (2 * f, d), 0.02, s.dtype),
@@ -246,20 +257,22 @@ def gen_tokens(vocab: int, n: int, seed: int, *key) -> np.ndarray:
 # ----------------------------------------------------------------------------- K/V, Q
 def gen_prefix_kv(s: ModelShape, seed: int, layer: int, seq: int, length: int):
     """Prefix K and V for one layer and sequence, drawn i.i.d. N(0,1) directly (K is
-    taken to be already rotated).  Returns two [n_heads, length, head_dim] arrays."""
-    k = _normal(_rng(seed, "pk", layer, seq), (s.n_heads, length, s.head_dim), 1.0, s.dtype)
-    v = _normal(_rng(seed, "pv", layer, seq), (s.n_heads, length, s.head_dim), 1.0, s.dtype)
+    taken to be already rotated).  Returns two [kv_heads, length, head_dim] arrays."""
+    k = _normal(_rng(seed, "pk", layer, seq), (s.kv_heads, length, s.head_dim), 1.0, s.dtype)
+    v = _normal(_rng(seed, "pv", layer, seq), (s.kv_heads, length, s.head_dim), 1.0, s.dtype)
     return k, v
 
 
 def gen_attention_case(seed: int, n_heads: int, head_dim: int, prefix: int, n: int,
-                       dtype: str = "bf16"):
+                       dtype: str = "bf16", n_kv_heads: int = 0):
     """Stand-alone tree-attention case (the sweep workload): Q for n tree nodes, K/V for
-    prefix+n slots, all N(0,1); a random parent array."""
+    prefix+n slots (n_kv_heads of them, default one per query head), all N(0,1); a random
+    parent array."""
     parent = tree_random(n, _rng(seed, "tree"))
+    hk = n_kv_heads or n_heads
     q = _normal(_rng(seed, "q"), (n, n_heads, head_dim), 1.0, dtype)
-    k = _normal(_rng(seed, "k"), (n_heads, prefix + n, head_dim), 1.0, dtype)
-    v = _normal(_rng(seed, "v"), (n_heads, prefix + n, head_dim), 1.0, dtype)
+    k = _normal(_rng(seed, "k"), (hk, prefix + n, head_dim), 1.0, dtype)
+    v = _normal(_rng(seed, "v"), (hk, prefix + n, head_dim), 1.0, dtype)
     return q, k, v, parent
 
 

@@ -31,18 +31,20 @@ def causal_forward(shape, weights, tokens):
     tokens = torch.as_tensor(tokens, dtype=torch.long)
     n = len(tokens)
     H, dh, Fd = shape.n_heads, shape.head_dim, shape.d_ffn
+    Hkv = getattr(shape, "n_kv_heads", 0) or H   # grouped-query: K/V heads repeated per group
     pos = torch.arange(n)
     x = _t(weights["embed"])[tokens]
     kv = []
     for w in weights["layers"]:
         h = F.rms_norm(x, (shape.d_model,), weight=_t(w["g_attn"]), eps=shape.rms_eps)
         qkv = F.linear(h, _t(w["wqkv"]))
-        q, k, v = qkv.split(H * dh, dim=-1)
+        q, k, v = qkv.split([H * dh, Hkv * dh, Hkv * dh], dim=-1)
         q = _rotate(q.reshape(n, H, dh), pos, shape.rope_theta).transpose(0, 1)
-        k = _rotate(k.reshape(n, H, dh), pos, shape.rope_theta).transpose(0, 1)
-        v = v.reshape(n, H, dh).transpose(0, 1)
+        k = _rotate(k.reshape(n, Hkv, dh), pos, shape.rope_theta).transpose(0, 1)
+        v = v.reshape(n, Hkv, dh).transpose(0, 1)
         kv.append((k.numpy().copy(), v.numpy().copy()))
-        o = F.scaled_dot_product_attention(q, k, v, is_causal=True)  # [H, n, dh]
+        o = F.scaled_dot_product_attention(q, k.repeat_interleave(H // Hkv, dim=0),
+                                           v.repeat_interleave(H // Hkv, dim=0), is_causal=True)  # [H, n, dh]
         x = x + F.linear(o.transpose(0, 1).reshape(n, H * dh), _t(w["wo"]))
         h2 = F.rms_norm(x, (shape.d_model,), weight=_t(w["g_ffn"]), eps=shape.rms_eps)
         g, u = F.linear(h2, _t(w["w_gate_up"])).split(Fd, dim=-1)

@@ -183,3 +183,75 @@ def test_kv_compact_index_map():
         assert np.array_equal(K[:, L + j], K0[:, L + pj])
         assert np.array_equal(V[:, L + j], V0[:, L + pj])
     assert np.array_equal(K[:, :L], K0[:, :L])
+
+
+# ----------------------------------------------------------------------------- grouped-query
+GQA_SMALL = I.ModelShape(2, 32, 4, 8, 64, 50, "f32", n_kv_heads=2)
+
+
+def expand_to_mha(shape, w):
+    """The multi-head model that a grouped-query model equals: every K/V head's rows of
+    Wk and Wv repeated for each query head of its group."""
+    from dataclasses import replace
+    H, Hkv, dh = shape.n_heads, shape.kv_heads, shape.head_dim
+    g = H // Hkv
+    out = dict(w)
+    out["layers"] = []
+    for lw in w["layers"]:
+        wq, wk, wv = np.split(lw["wqkv"], [H * dh, (H + Hkv) * dh])
+        rep = lambda m: np.repeat(m.reshape(Hkv, dh, -1), g, axis=0).reshape(H * dh, -1)
+        out["layers"].append(dict(lw, wqkv=np.concatenate([wq, rep(wk), rep(wv)])))
+    return replace(shape, n_kv_heads=0), out
+
+
+@pytest.mark.parametrize("seed,L,n", [(0, 5, 9), (1, 0, 7), (2, 12, 15)])
+def test_grouped_query_node_logits_equal_causal_forward_over_root_path(seed, L, n):
+    w, prefix, pkv = setup(GQA_SMALL, seed, L)
+    rng = np.random.default_rng(300 + seed)
+    parent = I.tree_c0() if n == 15 else I.tree_random(n, rng)
+    tok = rng.integers(0, GQA_SMALL.vocab, size=n)
+    kv = []
+    for l in range(GQA_SMALL.n_layers):
+        K = np.full((GQA_SMALL.kv_heads, L + n, GQA_SMALL.head_dim), np.nan)
+        V = np.full_like(K, np.nan)
+        if L:
+            K[:, :L], V[:, :L] = pkv[l]
+        kv.append((K, V))
+    logits = O.decoder_tree_forward(GQA_SMALL, w, kv, tok, parent, L)
+    for i in range(n):
+        string = list(prefix) + [int(tok[j]) for j in O.root_path(parent, i)]
+        want, _ = B.causal_forward(GQA_SMALL, w, string)
+        assert np.allclose(logits[i], want[-1], rtol=1e-9, atol=1e-11), i
+
+
+def test_grouped_query_equals_multi_head_with_repeated_kv_weights():
+    """Closed relation: sharing a K/V head between g query heads is the multi-head model
+    whose Wk, Wv rows are repeated g times (checked inside the oracle, both ways round)."""
+    w, prefix, pkv = setup(GQA_SMALL, 4, 6)
+    mha_shape, mha_w = expand_to_mha(GQA_SMALL, w)
+    rng = np.random.default_rng(9)
+    n, L = 11, 6
+    parent = I.tree_random(n, rng)
+    tok = rng.integers(0, GQA_SMALL.vocab, size=n)
+    def cache(shape, heads_kv):
+        out = []
+        for l in range(shape.n_layers):
+            K = np.zeros((heads_kv, L + n, shape.head_dim)); V = np.zeros_like(K)
+            k, v = pkv[l]
+            g = heads_kv // k.shape[0]
+            K[:, :L], V[:, :L] = np.repeat(k, g, axis=0), np.repeat(v, g, axis=0)
+            out.append((K, V))
+        return out
+    a = O.decoder_tree_forward(GQA_SMALL, w, cache(GQA_SMALL, 2), tok, parent, L)
+    b = O.decoder_tree_forward(mha_shape, mha_w, cache(mha_shape, 4), tok, parent, L)
+    assert np.allclose(a, b, rtol=1e-11, atol=1e-12)
+
+
+def test_grouped_query_attention_reads_the_group_head():
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((5, 6, 4)); k = rng.standard_normal((2, 9, 4)); v = rng.standard_normal((2, 9, 4))
+    parent = I.tree_chain(5)
+    got = O.tree_attention(q, k, v, parent, 4)
+    want = O.tree_attention(q, np.repeat(k, 3, axis=0), np.repeat(v, 3, axis=0), parent, 4)
+    assert np.allclose(got, want, rtol=0, atol=1e-14)
+    assert not np.allclose(got[:, 0], O.tree_attention(q, k[::-1].repeat(3, axis=0), v[::-1].repeat(3, axis=0), parent, 4)[:, 0])
