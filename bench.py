@@ -36,13 +36,14 @@ def build_device_model(shape, seed, torch, b):
     dw = b.DeviceWeights(desc)
     dt = torch.bfloat16
     d, hd, F, V = shape.d_model, shape.n_heads * shape.head_dim, shape.d_ffn, shape.vocab
+    kvd = shape.kv_heads * shape.head_dim
 
     def rnd(n_out, n_in):
         return (torch.randn(n_out, n_in, device="cuda", dtype=torch.float32, generator=gen) * 0.02).to(dt)
 
     ones = torch.ones(d, device="cuda", dtype=torch.float32)
     for _ in range(shape.n_layers):
-        dw.add_layer(ones, rnd(3 * hd, d), rnd(d, hd), ones, rnd(2 * F, d), rnd(d, F))
+        dw.add_layer(ones, rnd(hd + 2 * kvd, d), rnd(d, hd), ones, rnd(2 * F, d), rnd(d, F))
     dw.set_globals(rnd(V, d), ones, rnd(V, d))
     dw.finish()
     torch.cuda.synchronize()
@@ -53,8 +54,9 @@ def gemm_bytes(T, n_in, n_out, e=2):
     return n_out * n_in * e + T * (n_in + n_out) * e
 
 
-def attn_bytes(L, N, H, dh, e=2):
-    return 2 * (L + N) * H * dh * e + 2 * N * H * dh * e
+def attn_bytes(L, N, H, dh, e=2, Hkv=None):
+    """K and V of every K/V head once, q in and the output out."""
+    return 2 * (L + N) * (Hkv or H) * dh * e + 2 * N * H * dh * e
 
 
 def cpu_baseline(wl, n_sample_layers=None):
@@ -91,7 +93,7 @@ def cpu_baseline(wl, n_sample_layers=None):
     kv = []
     for l in range(n_sample_layers):
         k, v = I.gen_prefix_kv(small, wl.seed, l, 0, L)
-        K = np.zeros((shape.n_heads, L + n, shape.head_dim))
+        K = np.zeros((shape.kv_heads, L + n, shape.head_dim))
         V = np.zeros_like(K)
         K[:, :L], V[:, :L] = k, v
         kv.append((K, V))
@@ -124,7 +126,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C3", "C4"])
+    ap.add_argument("--workload", default="C1", choices=["C1", "C3", "C4", "G1"],
+                    help="C1 (default): the 7B workload the metric is quoted on; C3 long prefix, "
+                         "C4 packed batch, G1 grouped-query 8B shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-times", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
@@ -150,6 +154,7 @@ def main():
     wl = I.workload(args.workload)
     shape = wl.shape
     H, dh, nl = shape.n_heads, shape.head_dim, shape.n_layers
+    Hkv = shape.kv_heads
     N = wl.tree_size                      # rows per tree
     B = len(wl.prefix_len)                # sequences in the packed batch
     T = B * N
@@ -165,7 +170,7 @@ def main():
     i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(dev)
     parent, tok = i32(np.concatenate(trees)), i32(tok_h)
     node_off, kv_off, prefix = i32(np.arange(B + 1) * N), i32(kv_off_h), i32(wl.prefix_len)
-    stride = H * s_pool * dh
+    stride = Hkv * s_pool * dh
     max_slots = L + N
     # prefix K/V ~ N(0,1) (synthetic, written straight into the tiled pool)
     gen = torch.Generator(device=dev).manual_seed(wl.seed + 1)
@@ -200,12 +205,12 @@ def main():
     kernels = {}
     if not args.no_kernel_times:
         d, hd, F, V = shape.d_model, H * dh, shape.d_ffn, shape.vocab
-        attn_alg = sum(attn_bytes(l, N, H, dh) for l in wl.prefix_len)
-        alg = {"gemm_qkv": gemm_bytes(T, d, 3 * hd), "tree_attn": attn_alg,
+        attn_alg = sum(attn_bytes(l, N, H, dh, Hkv=Hkv) for l in wl.prefix_len)
+        alg = {"gemm_qkv": gemm_bytes(T, d, hd + 2 * Hkv * dh), "tree_attn": attn_alg,
                "gemm_o": gemm_bytes(T, hd, d), "gemm_gate_up": gemm_bytes(T, d, 2 * F) - T * F * 2,
                "gemm_down": gemm_bytes(T, F, d), "gemm_lm": T * d * 2 + V * d * 2 + T * V * 4,
                "attn_combine": 0, "reduce_norm": 0}
-        flops = {"gemm_qkv": 2 * T * d * 3 * hd, "gemm_o": 2 * T * hd * d, "gemm_gate_up": 2 * T * d * 2 * F,
+        flops = {"gemm_qkv": 2 * T * d * (hd + 2 * Hkv * dh), "gemm_o": 2 * T * hd * d, "gemm_gate_up": 2 * T * d * 2 * F,
                  "gemm_down": 2 * T * F * d, "gemm_lm": 2 * T * d * V,
                  "tree_attn": sum(4 * N * (l + N) * H * dh for l in wl.prefix_len)}
         for name in ("gemm_gate_up", "gemm_qkv", "gemm_down", "gemm_o", "gemm_lm", "tree_attn",
@@ -270,7 +275,7 @@ def main():
         prompt = [int(t) for t in rng.integers(0, shape.vocab, size=L + 1)]
         tmpl = I.tree_template(N, r_len, rng)
         sp = (L + 1 + n_new + N + 31) // 32 * 32
-        kp2 = torch.zeros(nl, H * sp * dh, device=dev, dtype=torch.bfloat16)
+        kp2 = torch.zeros(nl, Hkv * sp * dh, device=dev, dtype=torch.bfloat16)
         vp2 = torch.zeros_like(kp2)
 
         def gen(max_new):
@@ -278,7 +283,7 @@ def main():
                               dtype=torch.uint8, device=dev)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            res = b.tr_jacobi_generate(desc, dw.struct, kp2, vp2, H * sp * dh, sp, prompt, tmpl, r_len, 3,
+            res = b.tr_jacobi_generate(desc, dw.struct, kp2, vp2, Hkv * sp * dh, sp, prompt, tmpl, r_len, 3,
                                        max_new, -1, wl.seed, wsl)
             return res, time.perf_counter() - t0
 
@@ -340,15 +345,17 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: LLaMA-7B-shaped decoder bf16, 32 layers, d 4096, 32x128 heads, "
-                               f"FFN 11008, vocab {shape.vocab}, " +
+        "config": {"workload": f"{wl.name}: " + ("LLaMA-7B-shaped" if Hkv == H else "grouped-query 8B-shaped") +
+                               f" decoder bf16, {nl} layers, d {shape.d_model}, {H}x{dh} heads" +
+                               (f" ({Hkv} K/V heads)" if Hkv != H else "") +
+                               f", FFN {shape.d_ffn}, vocab {shape.vocab}, " +
                                (f"prefix {L}, {N}-node tree, batch 1" if B == 1 else
                                 f"{B} packed sequences, ragged prefixes {min(wl.prefix_len)}..{L}, {N}-node tree each"),
                    "tree_rows": T, "prefix_len": L if B == 1 else list(wl.prefix_len)},
         "tree_attn": kernels.get("tree_attn"),
         "step_hbm_lower_bound_ms": round((sum(p.numel() for p in dw._keep if p.dtype == torch.bfloat16) * 2
                                           - shape.vocab * shape.d_model * 2
-                                          + nl * sum(attn_bytes(l, N, H, dh) for l in wl.prefix_len))
+                                          + nl * sum(attn_bytes(l, N, H, dh, Hkv=Hkv) for l in wl.prefix_len))
                                          / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
         "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
         "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,

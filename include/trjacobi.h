@@ -36,7 +36,8 @@
  * kv_off[s] + prefix_len[s] + i.
  *
  * Data layouts (element offsets; elements are 2 bytes for TRJ_BF16, 4 for TRJ_F32)
- *  - KV pool, one layer: K and V each hold n_heads planes of s_pool * head_dim
+ *  - KV pool, one layer: K and V each hold one plane per K/V head (n_kv_heads, which is
+ *    n_heads unless the model uses grouped-query attention) of s_pool * head_dim
  *    elements (s_pool a multiple of TRJ_KV_BLOCK, head_dim a multiple of 32); K is
  *    stored already rotated.  Inside a plane the slots are tiled in blocks of 32 so
  *    that a wavefront's 16-byte-per-lane load is one contiguous 1 KiB read that is
@@ -88,11 +89,13 @@ typedef struct {
   float rms_eps;    /* RMSNorm: x * g / sqrt(mean(x^2) + rms_eps) */
   float rope_theta; /* rotary base; pair (j, j+head_dim/2), angle pos*theta^(-2j/head_dim) */
   int32_t dtype;    /* trj_dtype of weights, KV pool and q; accumulation is fp32 */
+  int32_t n_kv_heads; /* grouped-query attention: K/V heads, a divisor of n_heads; query head h
+                       * reads K/V head h / (n_heads / n_kv_heads).  0 means n_heads. */
 } trj_model_desc;
 
 typedef struct {
   const float* g_attn;   /* [d_model] */
-  const void* wqkv;      /* [3*n_heads*head_dim][d_model], TRJ_PACK_QKV */
+  const void* wqkv;      /* [(n_heads + 2*n_kv_heads)*head_dim][d_model], rows Wq;Wk;Wv, TRJ_PACK_QKV */
   const void* wo;        /* [d_model][n_heads*head_dim],   TRJ_PACK_PLAIN */
   const float* g_ffn;    /* [d_model] */
   const void* w_gate_up; /* [2*d_ffn][d_model],            TRJ_PACK_GATE_UP */
@@ -122,7 +125,7 @@ int32_t trj_pack_weight(void* dst, const void* src_rowmajor, int32_t n_out, int3
                         int32_t dtype, int32_t kind, int32_t n_heads, int32_t head_dim,
                         void* stream);
 /* plain [n_heads][n_slots][head_dim] <-> the tiled pool planes of one layer, slots
- * slot0 .. slot0+n_slots-1 of the pool. */
+ * slot0 .. slot0+n_slots-1 of the pool.  n_heads here counts planes, i.e. K/V heads. */
 int32_t trj_kv_pack(void* k_pool, void* v_pool, const void* k_plain, const void* v_plain,
                     int32_t n_heads, int32_t head_dim, int32_t s_pool, int32_t slot0,
                     int32_t n_slots, int32_t dtype, void* stream);
@@ -172,13 +175,16 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
  * head: softmax over {prefix slots 0..prefix_len[s]-1} U {tree slots of i's ancestors
  * and i itself} of scale * q.k, times V.  The tree's own K/V must already be in the
  * pool at slots kv_off[s] + prefix_len[s] + i.  q, out: [T][n_heads][head_dim] in
- * `dtype`.  max_seq_slots: host upper bound of prefix_len[s] + N_s (sizes the launch).
- * workspace: device scratch of at least trj_workspace_bytes(...) bytes. */
+ * `dtype`.  k_layer, v_layer hold n_kv_heads planes (0: n_heads); with fewer K/V heads
+ * than query heads, query head h reads plane h / (n_heads / n_kv_heads) (grouped-query
+ * attention).  max_seq_slots: host upper bound of prefix_len[s] + N_s (sizes the
+ * launch).  workspace: device scratch of at least trj_workspace_bytes(...) bytes. */
 int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
                        const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                        const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
-                       int32_t head_dim, int32_t s_pool, int32_t max_seq_slots, int32_t dtype,
-                       float scale, void* workspace, size_t ws_bytes, void* out, void* stream);
+                       int32_t n_kv_heads, int32_t head_dim, int32_t s_pool,
+                       int32_t max_seq_slots, int32_t dtype, float scale, void* workspace,
+                       size_t ws_bytes, void* out, void* stream);
 
 /* Greedy argmax (Eq. 1) and the longest accepted path (section "TR-Jacobi Decoding").
  * If logits != NULL: argmax_out[i] = lowest index of the row maximum of logits[i][0..V)
@@ -198,7 +204,7 @@ int32_t accept_path(const float* logits, const int32_t* tok, const int32_t* pare
  * j = 0..accept_len[s], slot kv_off+prefix_len+j <- slot kv_off+prefix_len+path[s][j]
  * for K and V; new_len[s] = prefix_len[s] + accept_len[s] + 1.  Sequences with
  * accept_len[s] < 0 are skipped (new_len = prefix_len).  Slots beyond new_len are
- * unspecified afterwards. */
+ * unspecified afterwards.  n_heads counts the planes of a layer, i.e. K/V heads. */
 int32_t kv_compact(void* k_pool, void* v_pool, size_t kv_layer_stride, const int32_t* path,
                    const int32_t* accept_len, const int32_t* kv_off, const int32_t* prefix_len,
                    int32_t B, int32_t n_layers, int32_t n_heads, int32_t head_dim,

@@ -125,8 +125,9 @@ def generate(shape, weights, prompt, parent, r, max_ngram, max_new, eos, seed):
         raise ValueError("bad sizes")
     n = len(parent)
     cap = len(prompt) + max_new + n
-    kv = [(np.full((shape.n_heads, cap, shape.head_dim), np.nan),
-           np.full((shape.n_heads, cap, shape.head_dim), np.nan)) for _ in range(shape.n_layers)]
+    hkv = getattr(shape, "n_kv_heads", 0) or shape.n_heads
+    kv = [(np.full((hkv, cap, shape.head_dim), np.nan),
+           np.full((hkv, cap, shape.head_dim), np.nan)) for _ in range(shape.n_layers)]
     # prompt pass: an ordinary causal forward is the chain-shaped tree on an empty prefix
     L = len(prompt) - 1
     if L > 0:

@@ -34,7 +34,8 @@ class TrjError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
+                ("n_kv_heads", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -69,7 +70,7 @@ _SIGS = {
     "trj_kv_unpack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "trj_linear": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp, _vp]),
     "trj_tree_mask": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
-    "tree_attention": (_i32, [_vp] * 7 + [_i32] * 7 + [_f, _vp, _sz, _vp, _vp]),
+    "tree_attention": (_i32, [_vp] * 7 + [_i32] * 8 + [_f, _vp, _sz, _vp, _vp]),
     "accept_path": (_i32, [_vp] * 4 + [_i32] * 3 + [_vp] * 7),
     "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
     "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
@@ -193,10 +194,10 @@ def trj_tree_mask(parent, node_off, B, T, depth, anc, status_dev):
 
 
 def tree_attention(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T, n_heads,
-                   head_dim, s_pool, max_seq_slots, dtype, scale, workspace, out):
+                   head_dim, s_pool, max_seq_slots, dtype, scale, workspace, out, n_kv_heads=0):
     _check("tree_attention", lib().tree_attention(
         _ptr(q), _ptr(k_layer), _ptr(v_layer), _ptr(parent), _ptr(node_off), _ptr(kv_off),
-        _ptr(prefix_len), B, T, n_heads, head_dim, s_pool, max_seq_slots, dtype, scale,
+        _ptr(prefix_len), B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), _stream()))
 
 
@@ -291,7 +292,8 @@ def tr_jacobi_generate(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_lay
 def make_desc(shape) -> ModelDesc:
     """ModelDesc from any object with the ModelShape fields (dtype "f32" / "bf16")."""
     return ModelDesc(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
-                     shape.vocab, shape.rms_eps, shape.rope_theta, BF16 if shape.dtype == "bf16" else F32)
+                     shape.vocab, shape.rms_eps, shape.rope_theta, BF16 if shape.dtype == "bf16" else F32,
+                     getattr(shape, "n_kv_heads", 0))
 
 
 class DeviceWeights:

@@ -81,6 +81,7 @@ static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int ma
 static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max_seq_slots,
                        bool need_logits, StepWs* w) {
   const int d = m.d_model, hd = m.n_heads * m.head_dim, F = m.d_ffn;
+  const int kvd = (m.n_kv_heads ? m.n_kv_heads : m.n_heads) * m.head_dim;
   carve_tree(c, m.dtype, B, T, m.n_heads, m.head_dim, max_seq_slots, &w->t);
   w->cs = c.take<float2>((size_t)T * (m.head_dim / 2));
   w->x = c.take<float>((size_t)T * d);
@@ -95,7 +96,7 @@ static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max
     w->partial = c.take<float>((size_t)(sk1 > sk2 ? sk1 : sk2) * T * d);
   } else {
     w->h = c.take<float>((size_t)T * d);
-    w->qkv = c.take<float>((size_t)T * 3 * hd);
+    w->qkv = c.take<float>((size_t)T * (hd + 2 * kvd));
     w->qf = c.take<float>((size_t)T * hd);
     w->of = c.take<float>((size_t)T * hd);
     w->gu = c.take<float>((size_t)T * 2 * F);
@@ -114,6 +115,8 @@ static int check_desc(const trj_model_desc* m) {
   if (m->dtype == TRJ_BF16 && m->head_dim != 64 && m->head_dim != 128) return TRJ_ERR_BAD_SHAPE;
   if (m->dtype == TRJ_BF16 && m->d_model > 8192) return TRJ_ERR_BAD_SHAPE;
   if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return TRJ_ERR_BAD_SHAPE;
+  if (m->n_kv_heads < 0 || (m->n_kv_heads > 0 && m->n_heads % m->n_kv_heads != 0))
+    return TRJ_ERR_BAD_SHAPE;
   return TRJ_OK;
 }
 
@@ -213,7 +216,10 @@ int32_t trj_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in,
   if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
   if (n_out < 32 || n_in < 16 || (n_out & 31) || (n_in & 15)) return TRJ_ERR_BAD_SHAPE;
   if (kind == TRJ_PACK_QKV) {
-    if (n_heads < 1 || head_dim < 32 || (head_dim & 31) || n_out != 3 * n_heads * head_dim)
+    // rows are [q: n_heads*dh | k | v] with k and v of equal size, kv heads dividing n_heads
+    const int kv_rows = head_dim > 0 ? n_out - n_heads * head_dim : 0;
+    if (n_heads < 1 || head_dim < 32 || (head_dim & 31) || kv_rows < 2 * head_dim ||
+        kv_rows % (2 * head_dim) != 0 || n_heads % (kv_rows / (2 * head_dim)) != 0)
       return TRJ_ERR_BAD_SHAPE;
   } else if (kind == TRJ_PACK_GATE_UP) {
     if (n_out & 63) return TRJ_ERR_BAD_SHAPE;
@@ -274,14 +280,17 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
 int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
                        const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                        const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
-                       int32_t head_dim, int32_t s_pool, int32_t max_seq_slots, int32_t dtype,
-                       float scale, void* workspace, size_t ws_bytes, void* out, void* stream) {
+                       int32_t n_kv_heads, int32_t head_dim, int32_t s_pool, int32_t max_seq_slots,
+                       int32_t dtype, float scale, void* workspace, size_t ws_bytes, void* out,
+                       void* stream) {
   if (!q || !k_layer || !v_layer || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
       !out)
     return TRJ_ERR_NULLPTR;
   if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
   TRJ_TRY(check_batch(B, T, s_pool, max_seq_slots));
   if (n_heads < 1 || head_dim < 32 || (head_dim & 31)) return TRJ_ERR_BAD_SHAPE;
+  if (n_kv_heads == 0) n_kv_heads = n_heads;
+  if (n_kv_heads < 1 || n_heads % n_kv_heads != 0) return TRJ_ERR_BAD_SHAPE;
   if (dtype == TRJ_BF16 && head_dim != 64 && head_dim != 128) return TRJ_ERR_BAD_SHAPE;
   if (dtype == TRJ_F32 && (size_t)(head_dim + max_seq_slots) * 4 > 64 * 1024)
     return TRJ_ERR_BAD_SHAPE;
@@ -299,12 +308,12 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
     TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
                                  (const uint16_t*)v_layer, w.anc, node_off, kv_off, prefix_len,
-                                 w.status, B, T, n_heads, head_dim, s_pool, max_seq_slots, scale,
+                                 w.status, B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, scale,
                                  w.attn, 0, 0, (uint16_t*)out, st);
   }
   return launch_tree_attn_f32((const float*)q, (const float*)k_layer, (const float*)v_layer, w.anc,
                               w.row_seq, node_off, kv_off, prefix_len, w.status, T, n_heads,
-                              head_dim, s_pool, max_seq_slots, scale, (float*)out, st);
+                              n_kv_heads, head_dim, s_pool, max_seq_slots, scale, (float*)out, st);
 }
 
 int32_t accept_path(const float* logits, const int32_t* tok, const int32_t* parent,
@@ -391,7 +400,8 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
   }
   TRJ_TRY(check_batch(B, T, s_pool, max_seq_slots));
   const int d = m.d_model, H = m.n_heads, dh = m.head_dim, hd = H * dh, F = m.d_ffn, V = m.vocab;
-  if (kv_layer_stride < (size_t)H * s_pool * dh || (long)m.n_layers * H > 65535)
+  const int Hkv = m.n_kv_heads ? m.n_kv_heads : H;  // K/V heads (grouped-query attention)
+  if (kv_layer_stride < (size_t)Hkv * s_pool * dh || (long)m.n_layers * Hkv > 65535)
     return TRJ_ERR_BAD_SHAPE;
   if (m.dtype == TRJ_F32 && (size_t)(dh + max_seq_slots) * 4 > 64 * 1024) return TRJ_ERR_BAD_SHAPE;
 
@@ -418,10 +428,10 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
       const trj_layer_weights& lw = weights->h_layers[l];
       uint16_t* kl = (uint16_t*)k_pool + (size_t)l * kv_layer_stride;
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
-      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, dh, s_pool, w.cs,
+      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, w.cs,
                               w.t.row_slot, w.q, kl, vl, st)); }
       TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, node_off, kv_off, prefix_len, status_dev,
-                                    B, T, H, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
+                                    B, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
                                     w.op, st));
       { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }
       { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st)); }
@@ -439,10 +449,10 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
       float* kl = (float*)k_pool + (size_t)l * kv_layer_stride;
       float* vl = (float*)v_pool + (size_t)l * kv_layer_stride;
       TRJ_TRY(launch_rmsnorm_f32(w.x, lw.g_attn, T, d, m.rms_eps, w.h, st));
-      TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.wqkv, T, d, 3 * hd, 0, w.qkv, st));
-      TRJ_TRY(launch_rope_kv_f32(w.qkv, w.cs, w.t.row_slot, T, H, dh, s_pool, w.qf, kl, vl, st));
+      TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.wqkv, T, d, (H + 2 * Hkv) * dh, 0, w.qkv, st));
+      TRJ_TRY(launch_rope_kv_f32(w.qkv, w.cs, w.t.row_slot, T, H, Hkv, dh, s_pool, w.qf, kl, vl, st));
       TRJ_TRY(launch_tree_attn_f32(w.qf, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off, prefix_len,
-                                   status_dev, T, H, dh, s_pool, max_seq_slots, scale, w.of, st));
+                                   status_dev, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.of, st));
       TRJ_TRY(launch_gemm_f32(w.of, (const float*)lw.wo, T, hd, d, 1, w.x, st));
       TRJ_TRY(launch_rmsnorm_f32(w.x, lw.g_ffn, T, d, m.rms_eps, w.h, st));
       TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.w_gate_up, T, d, 2 * F, 0, w.gu, st));
@@ -458,7 +468,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
                         path, bonus_tok, status_dev, st)); }
   ProfScope ps_(KC_KV_COMPACT, st);
   return launch_kv_compact(k_pool, v_pool, kv_layer_stride, path, accept_len, kv_off, prefix_len, B,
-                           m.n_layers, H, dh, s_pool, m.dtype, new_len, st);
+                           m.n_layers, Hkv, dh, s_pool, m.dtype, new_len, st);
 }
 
 // workspace bytes of one step_impl call (pure arithmetic)

@@ -37,7 +37,7 @@ struct AttnArgs {
   const int32_t* kv_off;
   const int32_t* prefix_len;
   const int32_t* status_dev;
-  int n_heads, s_pool, bpwg, nsplit_max, qg_max;
+  int n_heads, group, s_pool, bpwg, nsplit_max, qg_max;  // group = query heads per K/V head
   float scale_log2e;
   // un-normalised partials, one per (sequence, query tile, head, split), stored as the
   // image of the wavefront's accumulator registers: element (mt*16 + v)*64 + lane, so that
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
     for (int v = 0; v < 16; ++v) o[mt][v] = 0.f;
   float m = NEG_BIG, l = 0.f;
 
-  const size_t plane = (size_t)head * a.s_pool * DH;
+  const size_t plane = (size_t)(head / a.group) * a.s_pool * DH;  // the group's K/V head
   const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_layer + plane) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_layer + plane) + lane;
   const int blk_base = a.kv_off[s] >> 5;
@@ -423,9 +423,9 @@ size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int ns
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
                           const uint64_t* anc, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,
-                          const int32_t* status_dev, int B, int T, int n_heads, int dh, int s_pool,
-                          int max_seq_slots, float scale, float* ws, int tiled, int tp,
-                          uint16_t* out, hipStream_t st) {
+                          const int32_t* status_dev, int B, int T, int n_heads, int n_kv_heads,
+                          int dh, int s_pool, int max_seq_slots, float scale, float* ws, int tiled,
+                          int tp, uint16_t* out, hipStream_t st) {
   if (dh != 64 && dh != 128) return TRJ_ERR_BAD_SHAPE;
   int ntw, qg_max, bpwg, nsplit_max;
   attn_bf16_plan(B, T, n_heads, max_seq_slots, &ntw, &qg_max, &bpwg, &nsplit_max);
@@ -434,8 +434,8 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   float* po = ws;
   float* pm = ws + parts * (dh / 32 * 1024);
   float* pl = pm + parts * 32;
-  AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, s_pool,
-             bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
+  AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, n_heads / n_kv_heads,
+             s_pool, bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
   dim3 grid(nsplit_max * qg_max, n_heads, B);
   const int ks = ATTN_WAVES / ntw;
   size_t lds = (size_t)(ks / 2) * ntw * (dh / 32) * 16 * 64 * sizeof(float);

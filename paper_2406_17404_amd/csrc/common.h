@@ -70,8 +70,8 @@ __host__ __device__ inline int logical_row(int r, int kind, int n_out, int n_hea
     return i < 16 ? 16 * t + i : (n_out >> 1) + 16 * t + (i - 16);
   }
   if (kind == TRJ_PACK_QKV) {
-    int hd = n_heads * dh;
-    if (r >= 2 * hd) return r;  // v rows keep their order
+    // rows are [q: n_heads*dh | k: kv_heads*dh | v: kv_heads*dh]; v rows keep their order
+    if (r >= n_heads * dh + (n_out - n_heads * dh) / 2) return r;
     int head_base = (r / dh) * dh;
     int j = (r % dh) >> 5, i = r & 31;
     return head_base + (i < 16 ? 16 * j + i : (dh >> 1) + 16 * j + (i - 16));

@@ -14,7 +14,7 @@ __device__ inline int packed_row(int n, int kind, int n_out, int n_heads, int dh
     return n < f ? 32 * (n >> 4) + (n & 15) : 32 * ((n - f) >> 4) + 16 + ((n - f) & 15);
   }
   if (kind == TRJ_PACK_QKV) {
-    if (n >= 2 * n_heads * dh) return n;
+    if (n >= n_heads * dh + (n_out - n_heads * dh) / 2) return n;  // v rows
     int base = (n / dh) * dh, c = n % dh, half = dh >> 1;
     return c < half ? base + 32 * (c >> 4) + (c & 15) : base + 32 * ((c - half) >> 4) + 16 + ((c - half) & 15);
   }
@@ -123,10 +123,11 @@ int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, 
 // qkv[t][packed rows] -> q[t][head][c] (rotated), K (rotated) and V into the pool at the
 // row's slot.  One block per row, one thread per (head, j < dh/2).
 __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs,
-                                   const int32_t* __restrict__ row_slot, int n_heads, int dh,
-                                   int s_pool, float* __restrict__ q, float* __restrict__ k_layer,
-                                   float* __restrict__ v_layer) {
-  const int t = blockIdx.x, half = dh >> 1, hd = n_heads * dh, n_out = 3 * hd;
+                                   const int32_t* __restrict__ row_slot, int n_heads,
+                                   int n_kv_heads, int dh, int s_pool, float* __restrict__ q,
+                                   float* __restrict__ k_layer, float* __restrict__ v_layer) {
+  const int t = blockIdx.x, half = dh >> 1, hd = n_heads * dh, kvd = n_kv_heads * dh;
+  const int n_out = hd + 2 * kvd;
   const float* y = qkv + (size_t)t * n_out;
   const int slot = row_slot[t];
   if (slot < 0) return;  // row of a malformed sequence
@@ -136,24 +137,29 @@ __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* 
     int na = head * dh + j, nb = na + half;
     float qa = y[packed_row(na, TRJ_PACK_QKV, n_out, n_heads, dh)];
     float qb = y[packed_row(nb, TRJ_PACK_QKV, n_out, n_heads, dh)];
-    float ka = y[packed_row(hd + na, TRJ_PACK_QKV, n_out, n_heads, dh)];
-    float kb = y[packed_row(hd + nb, TRJ_PACK_QKV, n_out, n_heads, dh)];
     float* qo = q + ((size_t)t * n_heads + head) * dh;
     qo[j] = qa * c.x - qb * c.y;
     qo[j + half] = qb * c.x + qa * c.y;
+  }
+  for (int idx = threadIdx.x; idx < n_kv_heads * half; idx += blockDim.x) {
+    int head = idx / half, j = idx % half;
+    float2 c = cs[(size_t)t * half + j];
+    int na = head * dh + j, nb = na + half;
+    float ka = y[packed_row(hd + na, TRJ_PACK_QKV, n_out, n_heads, dh)];
+    float kb = y[packed_row(hd + nb, TRJ_PACK_QKV, n_out, n_heads, dh)];
     float* kp = k_layer + (size_t)head * s_pool * dh;
     float* vp = v_layer + (size_t)head * s_pool * dh;
     kp[k_off(slot, j, dh)] = ka * c.x - kb * c.y;
     kp[k_off(slot, j + half, dh)] = kb * c.x + ka * c.y;
-    vp[v_off(slot, j, dh)] = y[2 * hd + na];
-    vp[v_off(slot, j + half, dh)] = y[2 * hd + nb];
+    vp[v_off(slot, j, dh)] = y[hd + kvd + na];
+    vp[v_off(slot, j + half, dh)] = y[hd + kvd + nb];
   }
 }
 int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* row_slot, int T,
-                       int n_heads, int dh, int s_pool, float* q, float* k_layer, float* v_layer,
-                       hipStream_t st) {
-  rope_kv_f32_kernel<<<T, 256, 0, st>>>(qkv, cs, row_slot, n_heads, dh, s_pool, q, k_layer,
-                                        v_layer);
+                       int n_heads, int n_kv_heads, int dh, int s_pool, float* q, float* k_layer,
+                       float* v_layer, hipStream_t st) {
+  rope_kv_f32_kernel<<<T, 256, 0, st>>>(qkv, cs, row_slot, n_heads, n_kv_heads, dh, s_pool, q,
+                                        k_layer, v_layer);
   return check_launch();
 }
 
@@ -180,8 +186,8 @@ __global__ __launch_bounds__(64) void tree_attn_f32_kernel(
     const float* __restrict__ v_layer, const uint64_t* __restrict__ anc,
     const int32_t* __restrict__ row_seq, const int32_t* __restrict__ node_off,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ prefix_len,
-    const int32_t* __restrict__ status_dev, int n_heads, int dh, int s_pool, int max_slots,
-    float scale, float* __restrict__ out) {
+    const int32_t* __restrict__ status_dev, int n_heads, int group, int dh, int s_pool,
+    int max_slots, float scale, float* __restrict__ out) {
   extern __shared__ float lds[];
   float* qs = lds;            // dh
   float* sc = lds + dh;       // max_slots
@@ -195,8 +201,8 @@ __global__ __launch_bounds__(64) void tree_attn_f32_kernel(
     for (int c = lane; c < dh; c += 64) o[c] = 0.f;
     return;
   }
-  const float* kp = k_layer + (size_t)head * s_pool * dh;
-  const float* vp = v_layer + (size_t)head * s_pool * dh;
+  const float* kp = k_layer + (size_t)(head / group) * s_pool * dh;  // the group's K/V head
+  const float* vp = v_layer + (size_t)(head / group) * s_pool * dh;
   const float* qr = q + ((size_t)t * n_heads + head) * dh;
   for (int c = lane; c < dh; c += 64) qs[c] = qr[c];
   __syncthreads();
@@ -239,14 +245,15 @@ __global__ __launch_bounds__(64) void tree_attn_f32_kernel(
 int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_layer,
                          const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
                          const int32_t* kv_off, const int32_t* prefix_len,
-                         const int32_t* status_dev, int T, int n_heads, int dh, int s_pool,
-                         int max_slots, float scale, float* out, hipStream_t st) {
+                         const int32_t* status_dev, int T, int n_heads, int n_kv_heads, int dh,
+                         int s_pool, int max_slots, float scale, float* out, hipStream_t st) {
   size_t lds = (size_t)(dh + max_slots) * sizeof(float);
   if (lds > 64 * 1024) return TRJ_ERR_BAD_SHAPE;
   dim3 grid(T, n_heads);
   tree_attn_f32_kernel<<<grid, 64, lds, st>>>(q, k_layer, v_layer, anc, row_seq, node_off,
-                                              kv_off, prefix_len, status_dev, n_heads, dh,
-                                              s_pool, max_slots, scale, out);
+                                              kv_off, prefix_len, status_dev, n_heads,
+                                              n_heads / n_kv_heads, dh, s_pool, max_slots, scale,
+                                              out);
   return check_launch();
 }
 

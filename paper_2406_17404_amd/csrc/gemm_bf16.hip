@@ -79,14 +79,17 @@ struct EpiQKV {
   uint16_t* q;
   uint16_t* k_layer;
   uint16_t* v_layer;
-  int T, n_heads, dh, s_pool;
+  int T, n_heads, n_kv_heads, dh, s_pool;
   __device__ void operator()(const f32x16& acc, int tile, int ttile, int lane, int) const {
     int t = ttile * 32 + (lane & 31);
     if (t >= T) return;
     int slot = row_slot[t];
     if (slot < 0) return;
-    const int tph = dh >> 5, hd_tiles = n_heads * tph, half = dh >> 1;
-    const int sec = tile / hd_tiles, head = (tile % hd_tiles) / tph, jt = tile % tph;
+    // row tiles: n_heads*tph of q, then n_kv_heads*tph of k, then as many of v
+    const int tph = dh >> 5, q_tiles = n_heads * tph, kv_tiles = n_kv_heads * tph, half = dh >> 1;
+    const int sec = tile < q_tiles ? 0 : (tile < q_tiles + kv_tiles ? 1 : 2);
+    const int rel = tile - (sec == 0 ? 0 : (sec == 1 ? q_tiles : q_tiles + kv_tiles));
+    const int head = rel / tph, jt = rel % tph;
     const int hh = lane >> 5;
     if (sec < 2) {
       uint16_t* plane = k_layer + (size_t)head * s_pool * dh;
@@ -349,10 +352,10 @@ int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in,
 }
 
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int dh, int s_pool, const float2* cs, const int32_t* row_slot, uint16_t* q,
-                    uint16_t* k_layer, uint16_t* v_layer, hipStream_t st) {
-  EpiQKV e{cs, row_slot, q, k_layer, v_layer, T, n_heads, dh, s_pool};
-  return launch_gemm(xp, w, tp, n_in, 3 * n_heads * dh, 1, e, st);
+                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* row_slot,
+                    uint16_t* q, uint16_t* k_layer, uint16_t* v_layer, hipStream_t st) {
+  EpiQKV e{cs, row_slot, q, k_layer, v_layer, T, n_heads, n_kv_heads, dh, s_pool};
+  return launch_gemm(xp, w, tp, n_in, (n_heads + 2 * n_kv_heads) * dh, 1, e, st);
 }
 
 // ------------------------------------------------------------------ split-k sum + residual + RMSNorm

@@ -60,14 +60,14 @@ int launch_rmsnorm_f32(const float* x, const float* g, int T, int d, float eps, 
 int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, int add_to,
                     float* y, hipStream_t st);
 int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* row_slot, int T,
-                       int n_heads, int dh, int s_pool, float* q, float* k_layer, float* v_layer,
-                       hipStream_t st);
+                       int n_heads, int n_kv_heads, int dh, int s_pool, float* q, float* k_layer,
+                       float* v_layer, hipStream_t st);
 int launch_silu_mul_f32(const float* gu, int T, int F, float* act, hipStream_t st);
 int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_layer,
                          const uint64_t* anc, const int32_t* row_seq, const int32_t* node_off,
                          const int32_t* kv_off, const int32_t* prefix_len,
-                         const int32_t* status_dev, int T, int n_heads, int dh, int s_pool,
-                         int max_slots, float scale, float* out, hipStream_t st);
+                         const int32_t* status_dev, int T, int n_heads, int n_kv_heads, int dh,
+                         int s_pool, int max_slots, float scale, float* out, hipStream_t st);
 
 // gemm_bf16.hip
 int gemm_bf16_split_k(int n_out, int tp, int n_in);
@@ -77,8 +77,8 @@ int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, 
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
                         uint16_t* act, hipStream_t st);
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int dh, int s_pool, const float2* cs, const int32_t* row_slot, uint16_t* q,
-                    uint16_t* k_layer, uint16_t* v_layer, hipStream_t st);
+                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* row_slot,
+                    uint16_t* q, uint16_t* k_layer, uint16_t* v_layer, hipStream_t st);
 int launch_reduce_norm(const float* partial, int n_split, float* x, const float* g, int T, int d,
                        int tp, float eps, uint16_t* hp, hipStream_t st);
 int launch_sum_splits(const float* partial, int n_split, size_t n, float* y, hipStream_t st);
@@ -92,9 +92,9 @@ int launch_zero_bytes(void* p, size_t bytes, hipStream_t st);
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
                           const uint64_t* anc, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,
-                          const int32_t* status_dev, int B, int T, int n_heads, int dh, int s_pool,
-                          int max_seq_slots, float scale, float* ws, int tiled, int tp,
-                          uint16_t* out, hipStream_t st);
+                          const int32_t* status_dev, int B, int T, int n_heads, int n_kv_heads,
+                          int dh, int s_pool, int max_seq_slots, float scale, float* ws, int tiled,
+                          int tp, uint16_t* out, hipStream_t st);
 
 // api.hip: the forward pass behind tr_verify_step (with_head == false: decoder layers
 // only, for prompt passes), its workspace need, and the model-descriptor check

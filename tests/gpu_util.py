@@ -12,6 +12,10 @@ from paper_2406_17404_amd import inputs as I
 DEV = "cuda"
 
 
+def kv_heads(shape):
+    return getattr(shape, "n_kv_heads", 0) or shape.n_heads
+
+
 def tdtype(name):
     return torch.bfloat16 if name == "bf16" else torch.float32
 
@@ -92,7 +96,7 @@ def run_step(shape, desc, dw, batch, kp_h, vp_h, want_logits=True):
     pools after the step."""
     dt = tdtype(shape.dtype)
     kp, vp = to_dev(kp_h, dt), to_dev(vp_h, dt)
-    stride = shape.n_heads * batch.s_pool * shape.head_dim
+    stride = kv_heads(shape) * batch.s_pool * shape.head_dim
     ws = torch.empty(b.trj_workspace_bytes(desc, batch.T, batch.B, batch.max_seq_slots),
                      dtype=torch.uint8, device=DEV)
     B, T = batch.B, batch.T
@@ -117,7 +121,7 @@ def oracle_cache(shape, prefix_kv, L, n, pad=0):
     """fp64 cache [H, L+n+pad, dh] per layer holding the given prefix."""
     kv = []
     for l in range(shape.n_layers):
-        K = np.full((shape.n_heads, L + n + pad, shape.head_dim), np.nan)
+        K = np.full((kv_heads(shape), L + n + pad, shape.head_dim), np.nan)
         V = np.full_like(K, np.nan)
         if L:
             K[:, :L], V[:, :L] = prefix_kv[l]

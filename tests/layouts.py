@@ -43,11 +43,12 @@ def logical_rows(n_out, kind, n_heads=0, dh=0):
     if kind == "gate_up":
         return np.where(i < 16, 16 * t + i, n_out // 2 + 16 * t + (i - 16))
     if kind == "qkv":
-        hd = n_heads * dh
+        hd = n_heads * dh                 # q rows, then k rows and v rows of equal count
+        v_start = hd + (n_out - hd) // 2
         base = r // dh * dh
         j = (r % dh) // 32
         lr = base + np.where(i < 16, 16 * j + i, dh // 2 + 16 * j + (i - 16))
-        return np.where(r >= 2 * hd, r, lr)
+        return np.where(r >= v_start, r, lr)
     raise KeyError(kind)
 
 

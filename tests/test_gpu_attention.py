@@ -16,13 +16,14 @@ TOL = {"f32": 1e-5, "bf16": 1e-2}
 
 
 def run_attention(dtype, H, dh, cases, align=64, nan_fill=True, scale=None):
-    """cases: list of (q[n,H,dh], k[H,L+n,dh], v, parent, L).  Returns per-case outputs."""
+    """cases: list of (q[n,H,dh], k[Hkv,L+n,dh], v, parent, L).  Returns per-case outputs."""
+    Hkv = cases[0][1].shape[0]
     trees = [c[3] for c in cases]
     prefix = [c[4] for c in cases]
     batch = Batch(trees, prefix, align=align)
     fill = np.nan if nan_fill else 0.0
-    kp = np.full((H, batch.s_pool * dh), fill, np.float32)
-    vp = np.full((H, batch.s_pool * dh), fill, np.float32)
+    kp = np.full((Hkv, batch.s_pool * dh), fill, np.float32)
+    vp = np.full((Hkv, batch.s_pool * dh), fill, np.float32)
     for s, (q, k, v, parent, L) in enumerate(cases):
         layouts.kv_to_pool(k.astype(np.float32), v.astype(np.float32), batch.s_pool,
                            int(batch.kv_off_h[s]), kp, vp)
@@ -36,14 +37,14 @@ def run_attention(dtype, H, dh, cases, align=64, nan_fill=True, scale=None):
     sc = float(1.0 / np.sqrt(dh)) if scale is None else scale
     b.tree_attention(qd, to_dev(kp, dt), to_dev(vp, dt), batch.parent, batch.node_off, batch.kv_off,
                      batch.prefix, batch.B, batch.T, H, dh, batch.s_pool, batch.max_seq_slots, code,
-                     sc, ws, out)
+                     sc, ws, out, n_kv_heads=Hkv)
     torch.cuda.synchronize()
     o = out.float().cpu().numpy()
     return [o[batch.rows(s)] for s in range(batch.B)]
 
 
-def case(seed, H, dh, L, n, dtype, parent=None):
-    q, k, v, p = I.gen_attention_case(seed, H, dh, L, n, dtype)
+def case(seed, H, dh, L, n, dtype, parent=None, n_kv=0):
+    q, k, v, p = I.gen_attention_case(seed, H, dh, L, n, dtype, n_kv)
     return (q, k, v, p if parent is None else parent, L)
 
 
@@ -112,6 +113,16 @@ def test_packed_ragged_batch_repeated_with_cold_caches():
             first = got
         else:
             assert all(np.array_equal(a, c) for a, c in zip(first, got)), trial
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H,n_kv,L,n", [(8, 2, 300, 64), (4, 1, 33, 100), (6, 3, 0, 17)])
+def test_grouped_query_heads_share_kv_planes(dtype, H, n_kv, L, n):
+    dh = 128 if dtype == "bf16" else 64
+    cases = [case(300 + H + n, H, dh, L, n, dtype, n_kv=n_kv), case(301, H, dh, 77, 20, dtype, n_kv=n_kv)]
+    got = run_attention(dtype, H, dh, cases, align=32)
+    for g, c in zip(got, cases):
+        assert rel_err(g, O.tree_attention(*c)) <= TOL[dtype]
 
 
 def test_bf16_launch_shapes_give_the_same_answer():

@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("kind,n_out,n_in,H,dh", [
     ("plain", 96, 48, 0, 0), ("gate_up", 128, 64, 0, 0), ("qkv", 3 * 2 * 64, 32, 2, 64),
-    ("qkv", 3 * 3 * 128, 80, 3, 128), ("plain", 4096, 1024, 0, 0)])
+    ("qkv", 3 * 3 * 128, 80, 3, 128), ("plain", 4096, 1024, 0, 0),
+    ("qkv", (8 + 2 * 2) * 64, 48, 8, 64), ("qkv", (4 + 2 * 1) * 128, 32, 4, 128)])   # grouped-query
 def test_pack_weight(dtype, kind, n_out, n_in, H, dh):
     rng = np.random.default_rng(0)
     w = rng.integers(-100, 100, size=(n_out, n_in)).astype(np.float32)  # exact in bf16

@@ -37,7 +37,7 @@ def make_model(shape, seed, std=0.3):
 def hip_generate(shape, desc, dw, prompt, parent, r, max_ngram, max_new, eos, seed, slack=0):
     n = len(parent)
     s_pool = (len(prompt) + max_new + n + slack + 31) // 32 * 32
-    stride = shape.n_heads * s_pool * shape.head_dim
+    stride = shape.kv_heads * s_pool * shape.head_dim
     dt = tdtype(shape.dtype)
     kp = torch.full((shape.n_layers, stride), float("nan"), dtype=dt, device=DEV)
     vp = torch.full((shape.n_layers, stride), float("nan"), dtype=dt, device=DEV)
@@ -69,6 +69,18 @@ def test_fp32_loop_equals_oracle_loop_and_autoregressive_greedy(seed, n, r, plen
     assert hist == want["accept_hist"] and steps == want["n_steps"]
     if plen <= 20:
         assert toks == BF.greedy_decode(shape, w, prompt, max_new)
+
+
+def test_grouped_query_loop_equals_oracle_loop():
+    shape = I.ModelShape(2, 64, 4, 32, 128, 64, "f32", n_kv_heads=2)
+    w = make_model(shape, 6)
+    rng = np.random.default_rng(76)
+    prompt = [int(t) for t in rng.integers(0, shape.vocab, size=135)]
+    parent = I.tree_template(20, 4, rng)
+    desc, dw = device_weights(shape, w)
+    toks, hist, steps = hip_generate(shape, desc, dw, prompt, parent, 4, 3, 14, -1, 6)
+    want = LP.generate(shape, w, prompt, parent, 4, 3, 14, -1, 6)
+    assert toks == want["tokens"] and hist == want["accept_hist"] and steps == want["n_steps"]
 
 
 def test_eos_stops_generation_and_is_kept():

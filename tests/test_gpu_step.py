@@ -35,7 +35,7 @@ def prefix_normal(shape, seed, s, L):
 def run_and_check(shape, w, trees, toks, prefix_lens, prefix_kvs, tol):
     desc, dw = device_weights(shape, w)
     batch = Batch(trees, prefix_lens, toks)
-    H, dh = shape.n_heads, shape.head_dim
+    H, dh = shape.kv_heads, shape.head_dim
     kp, vp = nan_pool(shape.n_layers, H, batch.s_pool, dh, shape.dtype), nan_pool(
         shape.n_layers, H, batch.s_pool, dh, shape.dtype)
     for s in range(batch.B):
@@ -123,6 +123,23 @@ def test_small_bf16_model(n_tree, L):
     pkv = prefix_normal(shape, 77, 0, L) if L else None
     res, summary = run_and_check(shape, w, [tree], [tok], [L], [pkv], 1e-2)
     print("bf16 N=%d L=%d: logits rel err %.2e accept %d flips %d" % ((n_tree, L) + summary[0]))
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 1e-5), ("bf16", 1e-2)])
+@pytest.mark.parametrize("n_heads,n_kv", [(4, 2), (4, 1), (8, 2)])
+def test_grouped_query_model(dtype, tol, n_heads, n_kv):
+    """Grouped-query attention: n_heads query heads share n_kv K/V heads (the pool holds
+    n_kv planes per layer); whole step against the oracle, packed batch of two trees."""
+    dh = 128 if dtype == "bf16" else 64
+    shape = I.ModelShape(2, 256, n_heads, dh, 512, 512, dtype, n_kv_heads=n_kv)
+    w = I.gen_weights(shape, 88)
+    rng = np.random.default_rng(n_heads * 10 + n_kv)
+    trees = [I.tree_c1(40, rng), I.tree_random(9, rng)]
+    Ls = [150, 0]
+    toks = [I.gen_tokens(shape.vocab, len(t), 88, "tree", s) for s, t in enumerate(trees)]
+    pkvs = [prefix_normal(shape, 88, 0, 150), None]
+    res, summary = run_and_check(shape, w, trees, toks, Ls, pkvs, tol)
+    print("gqa %s %d/%d: logits rel err %.2e" % (dtype, n_heads, n_kv, max(e for e, _, _ in summary)))
 
 
 def test_packed_bf16_batch_with_ragged_prefixes():

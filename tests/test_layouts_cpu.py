@@ -15,5 +15,5 @@ def test_layout_formulas_are_bijections():
 
 def test_row_permutations_are_bijections():
     for kind, n, H, dh in (("plain", 96, 0, 0), ("gate_up", 128, 0, 0), ("qkv", 384, 2, 64),
-                           ("qkv", 3 * 3 * 128, 3, 128)):
+                           ("qkv", 3 * 3 * 128, 3, 128), ("qkv", (8 + 2 * 2) * 64, 8, 64)):
         assert sorted(layouts.logical_rows(n, kind, H, dh)) == list(range(n))

@@ -172,3 +172,12 @@ def test_generate_rejects_bad_templates():
         LP.generate(SMALL, w, [1, 2], np.array([-1, 0, 0], np.int32), 2, 3, 4, -1, 0)  # last 2 nodes are no chain
     with pytest.raises(ValueError):
         LP.generate(SMALL, w, [1, 2], np.array([-1, 1, 0], np.int32), 0, 3, 4, -1, 0)
+
+
+def test_generate_with_grouped_query_attention_equals_autoregressive_greedy():
+    from test_oracle_step import GQA_SMALL
+    w, _, _ = setup(GQA_SMALL, 5, 0)
+    prompt = [7, 3, 9, 3, 1, 4]
+    parent = template(10, 3, np.random.default_rng(5))
+    res = LP.generate(GQA_SMALL, w, prompt, parent, 3, 3, 12, -1, 5)
+    assert res["tokens"] == B.greedy_decode(GQA_SMALL, w, prompt, 12)
