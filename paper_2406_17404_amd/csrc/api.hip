@@ -150,6 +150,7 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
   if (!strcmp(name, "gemm_target_wgs")) g_tune.gemm_target_wgs = value;
   else if (!strcmp(name, "max_split_k")) g_tune.max_split_k = value;
   else if (!strcmp(name, "gemm_cfg")) g_tune.gemm_cfg = value;
+  else if (!strcmp(name, "gemm_big_t")) g_tune.gemm_big_t = value;
   else if (!strcmp(name, "attn_target_wgs")) g_tune.attn_target_wgs = value;
   else if (!strcmp(name, "attn_min_bpw")) g_tune.attn_min_bpw = value;
   else return TRJ_ERR_BAD_SHAPE;
@@ -360,7 +361,7 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   if (dtype == TRJ_F32)
     return launch_gemm_f32((const float*)x, (const float*)w_packed, T, n_in, n_out, 0, y, st);
   const int tp = padded_rows(T);
-  int sk = split_k > 0 ? gemm_bf16_clamp_split(tp, n_in, split_k) : gemm_bf16_split_k(n_out, tp, n_in);
+  int sk = split_k > 0 ? gemm_bf16_clamp_split(n_out, tp, n_in, split_k) : gemm_bf16_split_k(n_out, tp, n_in);
   Carver c(workspace);
   uint16_t* xp = c.take<uint16_t>((size_t)tp * n_in);
   float* part = c.take<float>((size_t)sk * T * n_out);

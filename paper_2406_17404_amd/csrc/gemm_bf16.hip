@@ -283,26 +283,177 @@ static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, in
   kern<<<grid, RT * KW * 64, lds, st>>>(a, epi);
 }
 
+// Many token rows (packed batches): the same structure with KW = 1, but every wavefront
+// owns WT row tiles, so that the MT activation operands it reads from LDS per k-step feed
+// WT * MT matrix instructions.  With one row tile per wavefront a k-step reads 4 KiB of
+// LDS per 4 instructions, which saturates the LDS (128 B/clk per CU) at about a quarter of
+// the matrix peak; two row tiles halve that.
+template <int MT, int RT, int WT, int PH, int PF, class Epi>
+__global__ __launch_bounds__(RT * 64) void gemm_t_kernel(GemmArgs a, Epi epi) {
+  constexpr int XG = PH * MT * 64;   // 16-byte granules per phase buffer
+  constexpr int XL = XG / (RT * 64);  // activation loads per lane and phase
+  static_assert(PH % PF == 0 && XG % (RT * 64) == 0, "phase shape");
+  extern __shared__ __align__(16) uint8_t smem[];
+  u32x4* lds = reinterpret_cast<u32x4*>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int rt = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ksteps = a.n_in >> 4;
+  const int nph = (ksteps + PH - 1) / PH;
+  const int ph0 = blockIdx.y * a.chunks_per_split;
+  const int ph1 = min(nph, ph0 + a.chunks_per_split);
+  // Workgroup ids go round-robin over the 8 dies (XCDs), each with its own L2.  The
+  // workgroups that stream the SAME weight rows (one per block of token rows) are given
+  // ids that land on one die, next to each other in its dispatch order, so that the rows
+  // come from HBM once and are shared through that die's L2; spread over the dies, or far
+  // apart in time, every token block re-streams them from HBM.
+  const int ttiles = a.tp >> 5, tblocks = ttiles / MT;
+  const int ntiles = a.n_out >> 5;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int tb = slot % tblocks, rg = (slot / tblocks) * 8 + xcd;
+  if (rg * RT * WT >= ntiles) return;  // padding of the row groups to a multiple of 8 (uniform)
+  const int tile0 = (rg * RT + rt) * WT;
+  const u32x4 zero = {0, 0, 0, 0};
+
+  f32x16 acc[WT][MT];
+#pragma unroll
+  for (int r = 0; r < WT; ++r)
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[r][m][v] = 0.f;
+
+  if (ph0 < ph1) {
+    const int n = (ph1 - ph0) * PH;  // k-steps of this wavefront
+    const u32x4* wp[WT];
+#pragma unroll
+    for (int r = 0; r < WT; ++r)
+      wp[r] = reinterpret_cast<const u32x4*>(a.w) + (size_t)min(tile0 + r, ntiles - 1) * ksteps * 64 + lane;
+    const u32x4* xg = reinterpret_cast<const u32x4*>(a.xp) + (size_t)tb * MT * 64;
+    // all indices are clamped, never predicated
+    auto w_load = [&](int i, int r) -> u32x4 {
+      int ks = min(ph0 * PH + min(i, n - 1), ksteps - 1);  // X is zero beyond n_in
+      return wp[r][(size_t)ks * 64];
+    };
+    u32x4 xa[XL];
+    auto x_load = [&](int ph) {
+      ph = min(ph, ph1 - 1);
+#pragma unroll
+      for (int j = 0; j < XL; ++j) {
+        int g = j * (RT * 64) + tid;
+        int ksl = g / (MT * 64), rem = g - ksl * (MT * 64);
+        xa[j] = xg[(size_t)min(ph * PH + ksl, ksteps - 1) * ttiles * 64 + rem];
+      }
+    };
+    auto x_store = [&](int buf, int ph) {
+#pragma unroll
+      for (int j = 0; j < XL; ++j) {
+        int g = j * (RT * 64) + tid;
+        int ks = ph * PH + g / (MT * 64);
+        lds[buf * XG + g] = ks < ksteps ? xa[j] : zero;
+      }
+    };
+    u32x4 wr[PF][WT];
+    x_load(ph0);
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+#pragma unroll
+      for (int r = 0; r < WT; ++r) wr[p][r] = w_load(p, r);
+    x_store(0, ph0);
+    x_load(ph0 + 1);
+    lds_barrier();
+    int i = 0;
+    u32x4 xb[2][MT];  // B operands of the current and the next k-step (LDS latency hidden)
+    for (int ph = ph0; ph < ph1; ++ph) {
+      const int buf = (ph - ph0) & 1;
+      const u32x4* xl = lds + buf * XG + lane;
+#pragma unroll
+      for (int m = 0; m < MT; ++m) xb[0][m] = xl[m * 64];
+#pragma unroll
+      for (int q = 0; q < PH; ++q) {
+        const int p = q % PF;
+        if (q + 1 < PH) {  // compile-time: request the next step's operands first
+#pragma unroll
+          for (int m = 0; m < MT; ++m) xb[(q + 1) & 1][m] = xl[((q + 1) * MT + m) * 64];
+        }
+#pragma unroll
+        for (int r = 0; r < WT; ++r) {
+          bf16x8 wa = __builtin_bit_cast(bf16x8, wr[p][r]);
+#pragma unroll
+          for (int m = 0; m < MT; ++m)
+            acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                wa, __builtin_bit_cast(bf16x8, xb[q & 1][m]), acc[r][m], 0, 0, 0);
+          wr[p][r] = w_load(i + q + PF, r);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep each reload next to its step
+      }
+      i += PH;
+      x_store(buf ^ 1, ph + 1);  // activations of the next phase (unused after the last one)
+      lds_barrier();
+      x_load(ph + 2);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < WT; ++r)
+    if (tile0 + r < ntiles) {
+#pragma unroll
+      for (int m = 0; m < MT; ++m) epi(acc[r][m], tile0 + r, tb * MT + m, lane, blockIdx.y);
+    }
+}
+
+constexpr int BIG_PH = 8, BIG_PF = 4;  // phase and ring of the many-rows kernel
+template <int MT, int RT, int WT, class Epi>
+static void launch_t(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
+                     int split_k, const Epi& epi, hipStream_t st) {
+  constexpr int PH = BIG_PH, PF = BIG_PF;
+  int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
+  if (split_k < 1) split_k = 1;
+  if (split_k > nph) split_k = nph;
+  int pps = (nph + split_k - 1) / split_k;
+  split_k = (nph + pps - 1) / pps;
+  GemmArgs a{xp, w, n_in, n_out, tp, pps};
+  const int rowgroups = (n_out / 32 + RT * WT - 1) / (RT * WT), tblocks = tp / (32 * MT);
+  dim3 grid((rowgroups + 7) / 8 * 8 * tblocks, split_k, 1);
+  size_t lds = (size_t)2 * PH * MT * 1024;
+  auto kern = gemm_t_kernel<MT, RT, WT, PH, PF, Epi>;
+  static bool big_lds_allowed = false;  // one-time, per instantiation
+  if (!big_lds_allowed) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    big_lds_allowed = true;
+  }
+  kern<<<grid, RT * 64, lds, st>>>(a, epi);
+}
+
 // (RT, KW) per shape: enough workgroups to cover the chip and enough wavefronts in flight
 // (about 700 x 16 KiB saturate HBM here), with as many rows per workgroup as that allows,
 // because a workgroup re-reads the whole activation slice for its rows.
 struct GemmPlan {
   int mt, rt, kw, ph, split_k;
+  bool big;
 };
 static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   GemmPlan g;
   g.mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
-  g.ph = g.mt == 4 ? 16 : 32;
-  int nph = ((n_in >> 4) + g.ph - 1) / g.ph;
+  const int ntiles = n_out >> 5, tblocks = tp / (32 * g.mt);
   if (split_k < 1) split_k = 1;
-  if (split_k > nph) split_k = nph;
-  int pps = (nph + split_k - 1) / split_k;
-  g.split_k = (nph + pps - 1) / pps;  // never an empty split
-  int ntiles = n_out >> 5, tblocks = tp / (32 * g.mt);
+  auto splits = [&](int ph) {  // grid splits a request really gets: never an empty one
+    int nph = ((n_in >> 4) + ph - 1) / ph;
+    int sk = split_k > nph ? nph : split_k;
+    int pps = (nph + sk - 1) / sk;
+    return (nph + pps - 1) / pps;
+  };
+  // many token rows: wavefronts that own two row tiles (see gemm_t_kernel), if that still
+  // gives the launch enough workgroups
+  g.big = g.mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t &&
+          (long)((ntiles + 7) / 8) * tblocks * splits(BIG_PH) >= 128;
+  g.ph = g.big ? BIG_PH : (g.mt == 4 ? 16 : 32);
+  g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt == 4 ? 3 : 2);
   g.rt = (shape == 1 || shape == 4) ? 4 : 2;
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : 2);
+  if (g.big) { g.rt = 4; g.kw = 1; }
   return g;
 }
 
@@ -319,14 +470,15 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
     else if (g.kw == 4) launch_p<M, 2, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);  \
     else launch_p<M, 2, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);                 \
   } while (0)
-  if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else TRJ_P(4);
+  if (g.big) launch_t<4, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
+  else if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else TRJ_P(4);
 #undef TRJ_P
   return check_launch();
 }
 
 // number of grid splits a request for split_k really gets
-int gemm_bf16_clamp_split(int tp, int n_in, int split_k) {
-  return plan_gemm(tp, n_in, 32, split_k).split_k;
+int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k) {
+  return plan_gemm(tp, n_in, n_out, split_k).split_k;
 }
 
 int gemm_bf16_split_k(int n_out, int tp, int n_in) {
@@ -334,9 +486,11 @@ int gemm_bf16_split_k(int n_out, int tp, int n_in) {
   // launch has about one workgroup (of 2 row tiles) per compute unit
   int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
   int groups = ((n_out / 32 + 1) / 2) * (tp / (32 * mt));
+  if (mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t)
+    groups = ((n_out / 32 + 7) / 8) * (tp / 128);  // 8 row tiles per workgroup there
   int sk = (g_tune.gemm_target_wgs + groups - 1) / groups;
   if (sk > g_tune.max_split_k) sk = g_tune.max_split_k;
-  return gemm_bf16_clamp_split(tp, n_in, sk);
+  return gemm_bf16_clamp_split(n_out, tp, n_in, sk);
 }
 
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,

@@ -8,7 +8,8 @@ namespace trj {
 struct Tunables {
   int gemm_target_wgs = 256;   // split-k is raised until a GEMM has this many workgroups
   int max_split_k = 8;
-  int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..3 force one
+  int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..4 force one
+  int gemm_big_t = 256;        // padded token rows from which wavefronts own two row tiles (0: never)
   int attn_target_wgs = 256;   // attention workgroups per launch aimed at (one per CU)
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
@@ -71,7 +72,7 @@ int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_la
 
 // gemm_bf16.hip
 int gemm_bf16_split_k(int n_out, int tp, int n_in);
-int gemm_bf16_clamp_split(int tp, int n_in, int split_k);
+int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k);
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
                           int n_out, int split_k, float* y, hipStream_t st);
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,

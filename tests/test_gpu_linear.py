@@ -29,7 +29,11 @@ def run_linear(dtype, T, n_in, n_out, split_k, seed=0):
 
 @pytest.mark.parametrize("T,n_in,n_out,split_k", [
     (1, 16, 32, 0), (15, 256, 96, 0), (64, 4096, 512, 1), (64, 4096, 512, 4), (33, 1040, 160, 3),
-    (128, 688, 96, 0), (100, 2048, 256, 2), (200, 512, 64, 0), (64, 11008, 128, 8)])
+    (128, 688, 96, 0), (100, 2048, 256, 2), (200, 512, 64, 0), (64, 11008, 128, 8),
+    # many rows: the kernel whose wavefronts own two row tiles (ragged row-tile count, split-k,
+    # a k-range that ends inside a phase, rows that are not a multiple of 128)
+    (256, 1024, 4096, 0), (512, 2064, 4128, 0), (1000, 512, 8192, 3), (1024, 4096, 2080, 2),
+    (300, 1024, 2048, 0)])
 def test_bf16_linear(T, n_in, n_out, split_k):
     got, want = run_linear("bf16", T, n_in, n_out, split_k)
     assert np.isfinite(got).all()
