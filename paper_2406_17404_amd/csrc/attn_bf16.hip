@@ -38,6 +38,7 @@ struct AttnArgs {
   const int32_t* prefix_len;
   const int32_t* status_dev;
   int n_heads, group, s_pool, bpwg, nsplit_max, qg_max;  // group = query heads per K/V head
+  int n_kv_groups;  // sequences x K/V heads x splits: sets of workgroups that share K/V blocks
   float scale_log2e;
   // un-normalised partials, one per (sequence, query tile, head, split), stored as the
   // image of the wavefront's accumulator registers: element (mt*16 + v)*64 + lane, so that
@@ -147,14 +148,23 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nt = wv % NTW, ks = wv / NTW;
-  const int head = blockIdx.y, s = blockIdx.z;
+  // Workgroup ids go round-robin over the 8 dies (XCDs), each with its own L2.  The
+  // workgroups that walk the SAME K/V blocks (the query groups of a head, and with
+  // grouped-query attention the query heads of a K/V head) get ids that fall on one die,
+  // next to each other in its dispatch order, so that the blocks come from HBM once.
+  const int members = a.group * a.qg_max;
+  const int slot = blockIdx.x >> 3, kvg = (slot / members) * 8 + (blockIdx.x & 7);
+  if (kvg >= a.n_kv_groups) return;  // padding to a multiple of 8 (uniform)
+  const int member = slot % members;
+  const int sp = kvg % a.nsplit_max, n_kv = a.n_heads / a.group;
+  const int head = ((kvg / a.nsplit_max) % n_kv) * a.group + member / a.qg_max;
+  const int s = kvg / (a.nsplit_max * n_kv), qg = member % a.qg_max;
   if (a.status_dev[s] != 0) return;  // uniform over the workgroup, before any barrier
   const int r0 = a.node_off[s], n = a.node_off[s + 1] - r0;
   const int L = a.prefix_len[s];
   const int total = L + n;
   const int nb = (total + 31) >> 5;
   const int nsplit = (nb + a.bpwg - 1) / a.bpwg;
-  const int qg = blockIdx.x % a.qg_max, sp = blockIdx.x / a.qg_max;
   if (sp >= nsplit || qg * 32 * NTW >= n) return;  // uniform as well
   const int b0 = sp * a.bpwg, b1 = min(nb, b0 + a.bpwg);
   const int n32 = lane & 31, hh = lane >> 5;
@@ -435,8 +445,10 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   float* pm = ws + parts * (dh / 32 * 1024);
   float* pl = pm + parts * 32;
   AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, n_heads / n_kv_heads,
-             s_pool, bpwg, nsplit_max, qg_max, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
-  dim3 grid(nsplit_max * qg_max, n_heads, B);
+             s_pool, bpwg, nsplit_max, qg_max, B * n_kv_heads * nsplit_max,
+             scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
+  const int members = n_heads / n_kv_heads * qg_max;
+  dim3 grid((B * n_kv_heads * nsplit_max + 7) / 8 * 8 * members);
   const int ks = ATTN_WAVES / ntw;
   size_t lds = (size_t)(ks / 2) * ntw * (dh / 32) * 16 * 64 * sizeof(float);
   {
