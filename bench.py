@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counters, scaled by the copy-probe
 # calibration (profiles/C1_kernel_hbm_traffic.md holds the run and the commands); workload C1
-MEASURED_TRAFFIC = {"C1": {"gemm_gate_up": 186.2e6, "gemm_qkv": 106.8e6, "tree_attn": 26.6e6,
+MEASURED_TRAFFIC = {"C1": {"gemm_gate_up": 186.2e6, "gemm_qkv": 106.7e6, "tree_attn": 26.0e6,
                            "gemm_lm": 274.7e6}}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -203,7 +203,12 @@ def main():
 
     # per-kernel launch durations, HIP events on the launch stream, same steps again
     kernels = {}
+    event_pair_us = None
     if not args.no_kernel_times:
+        # two events recorded back to back are this far apart; reported beside the bracketed
+        # durations below (which are NOT corrected by it: rocprofv3's kernel durations sit
+        # between the two figures, about 3 us below the bracketed one)
+        event_pair_us = b.trj_profile_event_overhead(512) * 1e3
         d, hd, F, V = shape.d_model, H * dh, shape.d_ffn, shape.vocab
         attn_alg = sum(attn_bytes(l, N, H, dh, Hkv=Hkv) for l in wl.prefix_len)
         alg = {"gemm_qkv": gemm_bytes(T, d, hd + 2 * Hkv * dh), "tree_attn": attn_alg,
@@ -357,7 +362,8 @@ def main():
                                           - shape.vocab * shape.d_model * 2
                                           + nl * sum(attn_bytes(l, N, H, dh, Hkv=Hkv) for l in wl.prefix_len))
                                          / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
-        "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roof, "kernels": kernels, "event_pair_us": event_pair_us and round(event_pair_us, 2),
+        "cpu_baseline": cpu,
         "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,
     }
     print(json.dumps(out))

@@ -156,6 +156,10 @@ int32_t trj_set_tunable(const char* name, int32_t value);
  * 10 accept, 11 KV compaction. */
 int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity);
 int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count);
+/* Average elapsed time between two events recorded back to back on `stream` (nothing
+ * between them): the part of a trj_profile_* duration that is the event pair itself, not
+ * the kernel it brackets.  `pairs` in 1..4096; synchronises the stream. */
+int32_t trj_profile_event_overhead(int32_t pairs, float* h_avg_ms, void* stream);
 
 /* Measurement aid: a plain copy of `bytes` (a multiple of 16) from src to dst, used to
  * calibrate the HBM traffic counters against a kernel whose traffic is known. */

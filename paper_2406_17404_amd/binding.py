@@ -63,6 +63,7 @@ _SIGS = {
     "trj_set_tunable": (_i32, [C.c_char_p, _i32]),
     "trj_profile_begin": (_i32, [_i32, _i32]),
     "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
+    "trj_profile_event_overhead": (_i32, [_i32, C.POINTER(C.c_float), _vp]),
     "trj_copy_probe": (_i32, [_vp, _vp, _sz, _vp]),
     "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
     "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -148,6 +149,13 @@ KERNEL_CLASSES = {"gemm_qkv": 1, "tree_attn": 2, "attn_combine": 3, "gemm_o": 4,
 
 def trj_profile_begin(kernel_class: int, capacity: int) -> None:
     _check("trj_profile_begin", lib().trj_profile_begin(kernel_class, capacity))
+
+
+def trj_profile_event_overhead(pairs: int = 256) -> float:
+    """Milliseconds between two events recorded back to back on the current stream."""
+    out = C.c_float(0)
+    _check("trj_profile_event_overhead", lib().trj_profile_event_overhead(pairs, C.byref(out), _stream()))
+    return float(out.value)
 
 
 def trj_profile_end(capacity: int) -> List[float]:

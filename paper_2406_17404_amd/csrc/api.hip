@@ -199,6 +199,33 @@ int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count) {
   return rc;
 }
 
+int32_t trj_profile_event_overhead(int32_t pairs, float* h_avg_ms, void* stream) {
+  if (!h_avg_ms) return TRJ_ERR_NULLPTR;
+  if (pairs < 1 || pairs > 4096) return TRJ_ERR_BAD_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<hipEvent_t> ev(2 * (size_t)pairs);
+  int rc = TRJ_OK;
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) rc = TRJ_ERR_HIP;
+  if (rc == TRJ_OK) {
+    for (int i = 0; i < pairs; ++i) {
+      (void)hipEventRecord(ev[2 * i], st);
+      (void)hipEventRecord(ev[2 * i + 1], st);
+    }
+    double sum = 0;
+    for (int i = 0; i < pairs; ++i) {
+      float ms = 0.f;
+      hipError_t e = hipEventSynchronize(ev[2 * i + 1]);
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
+      if (e != hipSuccess) { note_hip_error(e); rc = TRJ_ERR_HIP; }
+      sum += ms;
+    }
+    *h_avg_ms = (float)(sum / pairs);
+  }
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  return rc;
+}
+
 int32_t trj_workspace_bytes(const trj_model_desc* desc, int32_t t_max, int32_t b_max,
                             int32_t l_max, size_t* h_bytes) {
   if (!h_bytes) return TRJ_ERR_NULLPTR;
