@@ -17,6 +17,12 @@
 //  - the activation loads of a phase are issued at the start of the previous phase, so
 //    they are older than every W load issued since and waiting for them costs nothing;
 //  - a scheduling barrier keeps each W reload next to the step that freed its register.
+//
+// Packed batches (from 256 token rows) are a different regime: the weights are re-used by
+// every block of 128 rows, the product approaches the matrix units' rate, and what binds
+// it is LDS bandwidth and where the re-used weight rows come from.  gemm_t_kernel below
+// keeps the structure but gives every wavefront two row tiles and places the workgroups
+// that share weight rows on one die.
 #include "common.h"
 #include "kernels.h"
 
