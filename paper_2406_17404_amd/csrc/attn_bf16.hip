@@ -142,7 +142,7 @@ template <int DH, int NTW>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArgs a) {
   constexpr int KS = ATTN_WAVES / NTW, KSTEPS = DH / 16, MTV = DH / 32;
   constexpr int OW = MTV * 16 * 64;  // floats of one wavefront's O tile
-  extern __shared__ __align__(16) float red[];  // KS/2 * NTW * OW floats
+  extern __shared__ __align__(16) float red[];  // NTW * MTV * (KS-1) parts of 1024 floats
   __shared__ float sm_m[ATTN_WAVES][32], sm_l[ATTN_WAVES][32];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -281,56 +281,53 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[mt][v] *= sc;
   }
+  // Every key stream keeps the 32-column parts of the output tile it owns (part mt belongs
+  // to stream mt % KS) and hands the others over through LDS: one barrier, and the final
+  // sums and stores are spread over all wavefronts.  The order of the sum is fixed
+  // (own part first, then the other streams in ascending order): deterministic.
+  constexpr int PART = 16 * 64;  // floats of one 32-column part of a wavefront's tile
 #pragma unroll
-  for (int step = KS / 2; step >= 1; step >>= 1) {
-    if (ks >= step && ks < 2 * step) {
-      float* dst = red + ((ks - step) * NTW + nt) * OW + lane;
+  for (int mt = 0; mt < MTV; ++mt) {
+    const int owner = mt % KS;
+    if (ks != owner) {
+      float* dst = red + (((nt * MTV + mt) * (KS - 1)) + (ks < owner ? ks : ks - 1)) * PART + lane;
 #pragma unroll
-      for (int mt = 0; mt < MTV; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) dst[(mt * 16 + v) * 64] = o[mt][v];
+      for (int v = 0; v < 16; ++v) dst[v * 64] = o[mt][v];
     }
-    __syncthreads();
-    if (ks < step) {
-      const float* src = red + (ks * NTW + nt) * OW + lane;
-#pragma unroll
-      for (int mt = 0; mt < MTV; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[mt][v] += src[(mt * 16 + v) * 64];
-    }
-    __syncthreads();
   }
-
-  if (nsplit == 1) {
-    // the workgroup saw every key: write the normalised rows
-    if (ks == 0 && qrow >= 0) {
-      const float inv = 1.0f / lg;
+  __syncthreads();
+  const size_t pidx =
+      (((size_t)s * a.tiles_per_seq + qg * NTW + nt) * a.n_heads + head) * a.nsplit_max + sp;
+  if (nsplit != 1 && ks == 0 && hh == 0) {
+    a.pm[pidx * 32 + n32] = mg;
+    a.pl[pidx * 32 + n32] = lg;
+  }
+  const float inv = 1.0f / lg;
 #pragma unroll
-      for (int mt = 0; mt < MTV; ++mt)
+  for (int mt = 0; mt < MTV; ++mt) {
+    if (ks != mt % KS) continue;
+    const float* src = red + ((nt * MTV + mt) * (KS - 1)) * PART + lane;
+#pragma unroll
+    for (int k = 0; k < KS - 1; ++k)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mt][v] += src[(k * 16 + v) * 64];
+    if (nsplit == 1) {
+      // the workgroup saw every key: write the normalised rows
+      if (qrow >= 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           u32x2 v = {pack2bf(o[mt][4 * g] * inv, o[mt][4 * g + 1] * inv),
                      pack2bf(o[mt][4 * g + 2] * inv, o[mt][4 * g + 3] * inv)};
           attn_store_row<DH>(a, qrow, head, 32 * mt + 8 * g + 4 * hh, v);
         }
-    }
-    return;
-  }
-
-  // ---- un-normalised partial of this workgroup (merged by attn_combine_kernel): the
-  // whole register tile, rows that do not exist included (finite, never read back)
-  if (ks == 0) {
-    const size_t pidx =
-        (((size_t)s * a.tiles_per_seq + qg * NTW + nt) * a.n_heads + head) * a.nsplit_max + sp;
-    if (hh == 0) {
-      a.pm[pidx * 32 + n32] = mg;
-      a.pl[pidx * 32 + n32] = lg;
-    }
-    float* img = a.po + pidx * OW + lane;
+      }
+    } else {
+      // un-normalised partial (merged by attn_combine_kernel): the whole register tile,
+      // rows that do not exist included (finite, never read back)
+      float* img = a.po + pidx * OW + mt * PART + lane;
 #pragma unroll
-    for (int mt = 0; mt < MTV; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) img[(mt * 16 + v) * 64] = o[mt][v];
+      for (int v = 0; v < 16; ++v) img[v * 64] = o[mt][v];
+    }
   }
 }
 
@@ -450,7 +447,7 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   const int members = n_heads / n_kv_heads * qg_max;
   dim3 grid((B * n_kv_heads * nsplit_max + 7) / 8 * 8 * members);
   const int ks = ATTN_WAVES / ntw;
-  size_t lds = (size_t)(ks / 2) * ntw * (dh / 32) * 16 * 64 * sizeof(float);
+  size_t lds = (size_t)ntw * (dh / 32) * (ks - 1) * 16 * 64 * sizeof(float);  // parts handed over
   {
     ProfScope ps_(KC_ATTN, st);
 #define TRJ_ATTN(D, Q)                                                                        \
