@@ -141,9 +141,12 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
                    int32_t dtype, int32_t split_k, void* workspace, size_t ws_bytes, float* y,
                    void* stream);
 
-/* Launch-shape knobs for experiments: "gemm_target_wgs", "max_split_k",
- * "gemm_cfg", "attn_target_wgs", "attn_min_bpw".  Results do not depend on them beyond fp32
- * summation order. */
+/* Launch-shape knobs for experiments: "gemm_target_wgs" (workgroups a split-k projection
+ * is split up to), "max_split_k", "gemm_cfg" (0: choose the workgroup shape per
+ * projection, 1..4 force one), "gemm_big_t" (padded token rows from which the packed-batch
+ * projection kernel is used, 0: never), "attn_target_wgs" (attention workgroups aimed at
+ * per launch), "attn_min_bpw" (32-slot blocks per wavefront, at least).  Results do not
+ * depend on them beyond fp32 summation order.  Unknown name: TRJ_ERR_BAD_SHAPE. */
 int32_t trj_set_tunable(const char* name, int32_t value);
 
 /* Per-kernel timing for benchmarks.  Between trj_profile_begin(kernel_class, capacity)

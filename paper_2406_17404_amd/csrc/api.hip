@@ -144,15 +144,17 @@ extern "C" {
 const char* trj_version(void) { return "trjacobi 0.1 (gfx950)"; }
 int32_t trj_last_hip_error(void) { return g_last_hip_error.load(); }
 
-// Tuning knobs for experiments (not part of the documented interface).
+// Launch-shape knobs for experiments; values outside the range a launch plan can use are
+// refused (a zero here would otherwise divide by zero in the plan).
 int32_t trj_set_tunable(const char* name, int32_t value) {
   if (!name) return TRJ_ERR_NULLPTR;
-  if (!strcmp(name, "gemm_target_wgs")) g_tune.gemm_target_wgs = value;
-  else if (!strcmp(name, "max_split_k")) g_tune.max_split_k = value;
-  else if (!strcmp(name, "gemm_cfg")) g_tune.gemm_cfg = value;
-  else if (!strcmp(name, "gemm_big_t")) g_tune.gemm_big_t = value;
-  else if (!strcmp(name, "attn_target_wgs")) g_tune.attn_target_wgs = value;
-  else if (!strcmp(name, "attn_min_bpw")) g_tune.attn_min_bpw = value;
+  const bool positive = value >= 1 && value <= (1 << 20);
+  if (!strcmp(name, "gemm_target_wgs") && positive) g_tune.gemm_target_wgs = value;
+  else if (!strcmp(name, "max_split_k") && positive) g_tune.max_split_k = value;
+  else if (!strcmp(name, "gemm_cfg") && value >= 0 && value <= 4) g_tune.gemm_cfg = value;
+  else if (!strcmp(name, "gemm_big_t") && value >= 0) g_tune.gemm_big_t = value;
+  else if (!strcmp(name, "attn_target_wgs") && positive) g_tune.attn_target_wgs = value;
+  else if (!strcmp(name, "attn_min_bpw") && positive) g_tune.attn_min_bpw = value;
   else return TRJ_ERR_BAD_SHAPE;
   return TRJ_OK;
 }

@@ -46,3 +46,13 @@ def test_version_and_host_side_errors_need_no_gpu():
     assert l.trj_tree_mask(None, None, 1, 1, None, None, None, None) == -1
     assert l.accept_path(None, 1, 1, 1, 1, 1000, 8, 1, 1, 1, 1, 1, 1, None) == -4
     assert l.kv_compact(None, None, 0, None, None, None, None, 1, 1, 1, 64, 64, 0, None, None) == -1
+
+
+def test_tunables_refuse_unknown_names_and_unusable_values():
+    from paper_2406_17404_amd import binding as b
+    l = b.lib()
+    assert l.trj_set_tunable(b"no_such_knob", 1) == -2
+    assert l.trj_set_tunable(b"attn_target_wgs", 0) == -2      # would divide by zero in the plan
+    assert l.trj_set_tunable(b"gemm_cfg", 9) == -2
+    assert l.trj_set_tunable(None, 1) == -1
+    assert l.trj_set_tunable(b"attn_target_wgs", 256) == 0
