@@ -303,14 +303,35 @@ def main():
                 "note": "random-init weights: drafts are accepted as rarely as an untrained model's; "
                         "the round time is the figure of interest (step + one host exchange)"}
 
-    # ---- the standalone tree-attention entry point at the sweep sizes (prefix 2k..32k, 64-node
-    # random trees, 32 heads x 128), layers rotated so that no launch finds its K/V in a cache
+    # ---- planted acceptance: the Jacobi chain of the tree (nodes 0..7) is driven to its fixed
+    # point by running the step itself 7 times (Jacobi iteration: draft j+1 <- prediction at
+    # draft j), after which the step must accept all 7 drafts
+    planted = None
+    if B == 1 and not args.no_extras and wl.tree_kind == "c1":
+        tok_p = tok_h.copy()
+        for j in range(7):
+            b.tr_verify_step(desc, dw.struct, k_pool, v_pool, stride, s_pool, i32(tok_p), parent, node_off,
+                             kv_off, prefix, B, T, max_slots, ws, logits, outs["argmax"], outs["accept_len"],
+                             outs["best"], path, outs["bonus"], outs["new_len"], outs["status"])
+            tok_p[j + 1] = int(outs["argmax"][j].cpu())
+        b.tr_verify_step(desc, dw.struct, k_pool, v_pool, stride, s_pool, i32(tok_p), parent, node_off,
+                         kv_off, prefix, B, T, max_slots, ws, logits, outs["argmax"], outs["accept_len"],
+                         outs["best"], path, outs["bonus"], outs["new_len"], outs["status"])
+        a_len = int(outs["accept_len"][0].cpu())
+        planted = {"planted_drafts": 7, "accept_len": a_len, "emitted_tokens_per_step": a_len + 1,
+                   "note": "drafts = the chain's Jacobi fixed point, reached by iterating the step; "
+                           "not a throughput claim (random-init weights)"}
+        step()  # leave the pools as the timed steps left them
+
+    # ---- the standalone tree-attention entry point at the sweep sizes (prefix 512..32k, random
+    # trees of 16..128 nodes, 32 heads x 128), layers rotated so that no launch finds its K/V in a cache
     attn_sweep = None
     if B == 1 and not args.no_extras:
         attn_sweep = []
-        for Ls, Ns in ((2048, 64), (8192, 64), (8192, 128), (32768, 64)):
+        for Ls, Ns in ((512, 16), (512, 64), (512, 128), (2048, 16), (2048, 64), (2048, 128),
+                       (8192, 16), (8192, 64), (8192, 128), (32768, 64)):
             sp = (Ls + Ns + 63) // 64 * 64
-            n_rot = max(4, min(16, int(3e9 // (2 * H * sp * dh * 2))))
+            n_rot = max(4, min(32, int(3e9 // (2 * H * sp * dh * 2))))   # > 1 GB of distinct K/V
             qd = torch.randn(Ns, H, dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
             kps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
             vps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -365,6 +386,7 @@ def main():
         "roofline": roof, "kernels": kernels, "event_pair_us": event_pair_us and round(event_pair_us, 2),
         "cpu_baseline": cpu,
         "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,
+        "planted_acceptance": planted,
     }
     print(json.dumps(out))
 
