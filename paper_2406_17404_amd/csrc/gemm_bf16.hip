@@ -457,6 +457,9 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt == 4 ? 3 : 2);
+  // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
+  // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
+  if (shape == 1 && g.mt == 4 && g_tune.gemm_cfg == 0) shape = 4;
   g.rt = (shape == 1 || shape == 4) ? 4 : 2;
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : 2);
   if (g.big) { g.rt = 4; g.kw = 1; }
