@@ -236,16 +236,43 @@ def main():
                 k["TFLOPs"] = round(flops[name] / (avg_ms * 1e-3) / 1e12, 2)
                 k["frac_mfma"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
             kernels[name] = k
+        # the same durations without the cost of the event pair: the span from a launch of
+        # this class to the end of the launch that follows it in the step, minus that
+        # follower's own bracketed duration (the pair's cost is in both and cancels)
+        follower = {"gemm_qkv": "tree_attn", "tree_attn": "attn_combine", "attn_combine": "gemm_o",
+                    "gemm_o": "reduce_norm", "gemm_gate_up": "gemm_down", "gemm_down": "reduce_norm"}
+        for name, nxt in follower.items():
+            if not kernels[nxt]["launches_per_step"]:
+                continue
+            cap = args.steps * (2 * nl + 2)
+            b.trj_profile_begin_span(b.KERNEL_CLASSES[name], b.KERNEL_CLASSES[nxt], cap)
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            times = b.trj_profile_end(cap)
+            if len(times) != kernels[name]["launches_per_step"] * args.steps:
+                continue
+            net_ms = sum(times) / len(times) - kernels[nxt]["avg_us"] * 1e-3
+            k = kernels[name]
+            k["net_us"] = round(net_ms * 1e3, 2)
+            if k.get("alg_bytes"):
+                k["net_GBps"] = round(k["alg_bytes"] / (net_ms * 1e-3) / 1e9, 1)
 
     roof = None
     if kernels:
         dom = max((k for k in kernels if kernels[k].get("alg_bytes")),
                   key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])
         kd = kernels[dom]
-        roof = {"kernel": dom, "bound": "hbm", "achieved": kd["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(kd["GBps"] / HBM_PEAK_GBS, 4),
+        # achieved: from the net duration (the event pair's own cost cancelled, see above),
+        # which is the figure that rocprofv3's kernel trace reproduces; the bracketed
+        # duration, a few microseconds longer, is reported beside it
+        us = kd.get("net_us", kd["avg_us"])
+        gbps = kd.get("net_GBps", kd["GBps"])
+        roof = {"kernel": dom, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
-                "avg_launch_us": kd["avg_us"], "alg_bytes_per_launch": kd["alg_bytes"]}
+                "avg_launch_us": us, "avg_launch_us_bracketed": kd["avg_us"],
+                "alg_bytes_per_launch": kd["alg_bytes"]}
 
     # ---- one sequence only: cost of the step against the number of tree rows (a chain of
     # n nodes is plain Jacobi decoding with n - 1 drafts, n = 1 is autoregressive decoding),

@@ -158,6 +158,11 @@ int32_t trj_set_tunable(const char* name, int32_t value);
  * sum + residual + RMSNorm, 6 gate/up projection, 7 down projection, 8 LM head, 9 argmax,
  * 10 accept, 11 KV compaction. */
 int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity);
+/* The same with a span: the start event goes before a launch of `first_class`, the stop
+ * event after the next launch of `last_class` (which the entry point issues later in the
+ * same step).  The difference between a span [A..B] and the single class B is the
+ * duration of A up to the start of B without the cost of the event pair itself. */
+int32_t trj_profile_begin_span(int32_t first_class, int32_t last_class, int32_t capacity);
 int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count);
 /* Average elapsed time between two events recorded back to back on `stream` (nothing
  * between them): the part of a trj_profile_* duration that is the event pair itself, not

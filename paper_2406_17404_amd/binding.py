@@ -62,6 +62,7 @@ _SIGS = {
     "trj_last_hip_error": (_i32, []),
     "trj_set_tunable": (_i32, [C.c_char_p, _i32]),
     "trj_profile_begin": (_i32, [_i32, _i32]),
+    "trj_profile_begin_span": (_i32, [_i32, _i32, _i32]),
     "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
     "trj_profile_event_overhead": (_i32, [_i32, C.POINTER(C.c_float), _vp]),
     "trj_copy_probe": (_i32, [_vp, _vp, _sz, _vp]),
@@ -149,6 +150,10 @@ KERNEL_CLASSES = {"gemm_qkv": 1, "tree_attn": 2, "attn_combine": 3, "gemm_o": 4,
 
 def trj_profile_begin(kernel_class: int, capacity: int) -> None:
     _check("trj_profile_begin", lib().trj_profile_begin(kernel_class, capacity))
+
+
+def trj_profile_begin_span(first_class: int, last_class: int, capacity: int) -> None:
+    _check("trj_profile_begin_span", lib().trj_profile_begin_span(first_class, last_class, capacity))
 
 
 def trj_profile_event_overhead(pairs: int = 256) -> float:

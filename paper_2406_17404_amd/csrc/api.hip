@@ -15,19 +15,20 @@ void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 
 // ---- optional per-kernel timing (trj_profile_begin / trj_profile_end)
 struct Profiler {
-  int cls = KC_NONE;
+  int cls = KC_NONE;       // class whose launch opens a timed span
+  int cls_last = KC_NONE;  // class whose launch closes it (the same class: one launch)
   std::vector<hipEvent_t> start, stop;
   int used = 0;
   bool open = false;
 };
 static Profiler g_prof;
 void prof_begin(int cls, hipStream_t st) {
-  if (cls != g_prof.cls || g_prof.used >= (int)g_prof.start.size()) return;
+  if (cls != g_prof.cls || g_prof.open || g_prof.used >= (int)g_prof.start.size()) return;
   (void)hipEventRecord(g_prof.start[g_prof.used], st);
   g_prof.open = true;
 }
 void prof_end(int cls, hipStream_t st) {
-  if (cls != g_prof.cls || !g_prof.open) return;
+  if (cls != g_prof.cls_last || !g_prof.open) return;
   (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
   g_prof.open = false;
 }
@@ -163,8 +164,13 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
 // chosen kernel class is bracketed by HIP events on its stream (this is the one place
 // where the library creates HIP objects: the events).  trj_profile_end waits for them and
 // returns the durations in milliseconds.
+int32_t trj_profile_begin_span(int32_t first_class, int32_t last_class, int32_t capacity);
 int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity) {
-  if (g_prof.cls != KC_NONE || kernel_class <= KC_NONE || kernel_class > KC_SETUP || capacity < 1)
+  return trj_profile_begin_span(kernel_class, kernel_class, capacity);
+}
+int32_t trj_profile_begin_span(int32_t kernel_class, int32_t last_class, int32_t capacity) {
+  if (g_prof.cls != KC_NONE || kernel_class <= KC_NONE || kernel_class > KC_SETUP ||
+      last_class <= KC_NONE || last_class > KC_SETUP || capacity < 1)
     return TRJ_ERR_BAD_SHAPE;
   g_prof.start.resize(capacity);
   g_prof.stop.resize(capacity);
@@ -178,6 +184,7 @@ int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity) {
   g_prof.used = 0;
   g_prof.open = false;
   g_prof.cls = kernel_class;
+  g_prof.cls_last = last_class;
   return TRJ_OK;
 }
 int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count) {
@@ -198,6 +205,8 @@ int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count) {
   g_prof.stop.clear();
   g_prof.used = 0;
   g_prof.cls = KC_NONE;
+  g_prof.cls_last = KC_NONE;
+  g_prof.open = false;
   return rc;
 }
 
