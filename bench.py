@@ -242,7 +242,7 @@ def main():
         follower = {"gemm_qkv": "tree_attn", "tree_attn": "attn_combine", "attn_combine": "gemm_o",
                     "gemm_o": "reduce_norm", "gemm_gate_up": "gemm_down", "gemm_down": "reduce_norm"}
         for name, nxt in follower.items():
-            if not kernels[nxt]["launches_per_step"]:
+            if not kernels[nxt]["launches_per_step"] or not kernels[name]["launches_per_step"]:
                 continue
             cap = args.steps * (2 * nl + 2)
             b.trj_profile_begin_span(b.KERNEL_CLASSES[name], b.KERNEL_CLASSES[nxt], cap)

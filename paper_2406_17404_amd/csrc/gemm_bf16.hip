@@ -180,7 +180,9 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
       i = min(i, n - 1);
       int ph = i / WS, s = i - ph * WS;
       int ks = min((ph0 + ph) * PH + kw * WS + s, ksteps - 1);  // X is zero beyond n_in
-      return wp[(size_t)ks * 64];
+      // weights are read once per launch: the streaming hint keeps them from displacing
+      // the activations in the caches and measurably raises the rate of the stream
+      return __builtin_nontemporal_load(wp + (size_t)ks * 64);
     };
     u32x4 xa[XL];
     auto x_load = [&](int ph) {
