@@ -23,8 +23,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counters, scaled by the copy-probe
 # calibration (profiles/C1_kernel_hbm_traffic.md holds the run and the commands); workload C1
-MEASURED_TRAFFIC = {"C1": {"gemm_gate_up": 186.2e6, "gemm_qkv": 106.7e6, "tree_attn": 26.0e6,
-                           "gemm_lm": 274.7e6}}
+MEASURED_TRAFFIC = {"C1": {"gemm_gate_up": 186.3e6, "gemm_qkv": 107.5e6, "tree_attn": 26.0e6,
+                           "gemm_lm": 275.0e6}}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
