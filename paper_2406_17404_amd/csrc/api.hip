@@ -50,7 +50,9 @@ struct Carver {
 struct TreeWs {
   int32_t *depth, *row_slot, *row_pos, *row_seq, *status;
   uint64_t* anc;
-  float* attn;  // bf16 attention partials
+  float* attn;     // bf16 attention partials
+  int32_t* items;  // bf16 attention work items and their count
+  int attn_rows, attn_qg;  // rows per item, items per sequence at most
 };
 struct StepWs {
   TreeWs t;
@@ -72,10 +74,15 @@ static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int ma
   w->status = c.take<int32_t>(B);
   w->anc = c.take<uint64_t>(2 * (size_t)T);
   w->attn = nullptr;
+  w->items = nullptr;
+  w->attn_rows = w->attn_qg = 0;
   if (dtype == TRJ_BF16) {
     int ntw, qg, bpwg, ns;
     attn_bf16_plan(B, T, H, max_seq_slots, &ntw, &qg, &bpwg, &ns);
     w->attn = c.take<float>(attn_bf16_ws_floats(B, qg * ntw, H, dh, ns));
+    w->items = c.take<int32_t>(ATTN_ITEM_WORDS(B, qg));
+    w->attn_rows = 32 * ntw;
+    w->attn_qg = qg;
   }
 }
 
@@ -345,9 +352,10 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   if (dtype == TRJ_BF16) {
     // rows of malformed sequences read as zeros
     TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
+    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, w.status, B, w.attn_rows, w.attn_qg, w.items, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
                                  (const uint16_t*)v_layer, w.anc, node_off, kv_off, prefix_len,
-                                 w.status, B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, scale,
+                                 w.status, w.items, B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, scale,
                                  w.attn, 0, 0, (uint16_t*)out, st);
   }
   return launch_tree_attn_f32((const float*)q, (const float*)k_layer, (const float*)v_layer, w.anc,
@@ -459,6 +467,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
+    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg, w.t.items, st));
     // attention output: padding rows and rows of malformed sequences stay zero all step
     TRJ_TRY(launch_zero_bytes(w.op, (size_t)tp * hd * 2, st));
     { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
@@ -470,7 +479,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
       { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, w.cs,
                               w.t.row_slot, w.q, kl, vl, st)); }
       TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, node_off, kv_off, prefix_len, status_dev,
-                                    B, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
+                                    w.t.items, B, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
                                     w.op, st));
       { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }
       { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st)); }

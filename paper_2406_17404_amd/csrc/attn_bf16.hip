@@ -38,7 +38,15 @@ struct AttnArgs {
   const int32_t* prefix_len;
   const int32_t* status_dev;
   int n_heads, group, s_pool, bpwg, nsplit_max, qg_max;  // group = query heads per K/V head
-  int n_kv_groups;  // sequences x K/V heads x splits: sets of workgroups that share K/V blocks
+  int n_kv_groups;  // items x K/V heads x splits: sets of workgroups that share K/V blocks
+  // work items (sequence, query group) that exist, longest sequence first, and their number
+  // (written by the prep kernels): workgroups past the list's end leave at once, and they
+  // are the LAST ids of the launch, so the live ones spread evenly over the compute units
+  // One record of 8 words per item: sequence, query group, first row, rows, prefix
+  // length, first K/V block of the sequence; a workgroup needs nothing else from memory to
+  // find its work, and reads record and count together.
+  const int32_t* items;
+  const int32_t* n_items;
   float scale_log2e;
   // un-normalised partials, one per (sequence, query tile, head, split), stored as the
   // image of the wavefront's accumulator registers: element (mt*16 + v)*64 + lane, so that
@@ -149,19 +157,19 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nt = wv % NTW, ks = wv / NTW;
   // Workgroup ids go round-robin over the 8 dies (XCDs), each with its own L2.  The
-  // workgroups that walk the SAME K/V blocks (the query groups of a head, and with
-  // grouped-query attention the query heads of a K/V head) get ids that fall on one die,
-  // next to each other in its dispatch order, so that the blocks come from HBM once.
-  const int members = a.group * a.qg_max;
-  const int slot = blockIdx.x >> 3, kvg = (slot / members) * 8 + (blockIdx.x & 7);
+  // workgroups that walk the SAME K/V blocks (with grouped-query attention the query heads
+  // of a K/V head) get ids that fall on one die, next to each other in its dispatch order,
+  // so that the blocks come from HBM once; the query groups of one sequence are
+  // neighbours in the item list, which puts them n_kv * nsplit_max ids apart on the same
+  // die whenever that product is a multiple of 8.
+  const int slot = blockIdx.x >> 3, kvg = (slot / a.group) * 8 + (blockIdx.x & 7);
   if (kvg >= a.n_kv_groups) return;  // padding to a multiple of 8 (uniform)
-  const int member = slot % members;
   const int sp = kvg % a.nsplit_max, n_kv = a.n_heads / a.group;
-  const int head = ((kvg / a.nsplit_max) % n_kv) * a.group + member / a.qg_max;
-  const int s = kvg / (a.nsplit_max * n_kv), qg = member % a.qg_max;
-  if (a.status_dev[s] != 0) return;  // uniform over the workgroup, before any barrier
-  const int r0 = a.node_off[s], n = a.node_off[s + 1] - r0;
-  const int L = a.prefix_len[s];
+  const int head = ((kvg / a.nsplit_max) % n_kv) * a.group + slot % a.group;
+  const int item = kvg / (a.nsplit_max * n_kv);
+  const int32_t* rec = a.items + (size_t)item * 8;  // inside the list's memory for every id
+  const int s = rec[0], qg = rec[1], r0 = rec[2], n = rec[3], L = rec[4], blk_base = rec[5];
+  if (item >= a.n_items[0]) return;  // uniform over the workgroup, before any barrier
   const int total = L + n;
   const int nb = (total + 31) >> 5;
   const int nsplit = (nb + a.bpwg - 1) / a.bpwg;
@@ -197,7 +205,6 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   const size_t plane = (size_t)(head / a.group) * a.s_pool * DH;  // the group's K/V head
   const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_layer + plane) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_layer + plane) + lane;
-  const int blk_base = a.kv_off[s] >> 5;
   u32x4 kreg[KSTEPS], vreg[MTV][2];
   auto load_k = [&](int b) {
     const u32x4* kb = kp + (size_t)(blk_base + b) * KSTEPS * 64;
@@ -413,7 +420,12 @@ void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int*
   const int ks = ATTN_WAVES / *ntw;
   int nb = (max_seq_slots + 31) / 32;
   if (nb < 1) nb = 1;
-  long cols = (long)B * n_heads * *qg_max;
+  // the host does not know the trees' sizes (they are device data): the number of work
+  // items lies between max(B, T / rows per item) and B * qg_max; the lower figure sizes
+  // the split (too few workgroups cost more than too many), the upper one the launch
+  const int rows = 32 * *ntw;
+  const int items_est = B > (T + rows - 1) / rows ? B : (T + rows - 1) / rows;
+  long cols = (long)items_est * n_heads;
   int b = (int)((nb * cols + g_tune.attn_target_wgs - 1) / g_tune.attn_target_wgs);
   if (b < g_tune.attn_min_bpw * ks) b = g_tune.attn_min_bpw * ks;
   if (b > nb) b = nb;
@@ -430,9 +442,9 @@ size_t attn_bf16_ws_floats(int B, int tiles_per_seq, int n_heads, int dh, int ns
 int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint16_t* v_layer,
                           const uint64_t* anc, const int32_t* node_off,
                           const int32_t* kv_off, const int32_t* prefix_len,
-                          const int32_t* status_dev, int B, int T, int n_heads, int n_kv_heads,
-                          int dh, int s_pool, int max_seq_slots, float scale, float* ws, int tiled,
-                          int tp, uint16_t* out, hipStream_t st) {
+                          const int32_t* status_dev, const int32_t* items, int B, int T,
+                          int n_heads, int n_kv_heads, int dh, int s_pool, int max_seq_slots,
+                          float scale, float* ws, int tiled, int tp, uint16_t* out, hipStream_t st) {
   if (dh != 64 && dh != 128) return TRJ_ERR_BAD_SHAPE;
   int ntw, qg_max, bpwg, nsplit_max;
   attn_bf16_plan(B, T, n_heads, max_seq_slots, &ntw, &qg_max, &bpwg, &nsplit_max);
@@ -442,10 +454,10 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   float* pm = ws + parts * (dh / 32 * 1024);
   float* pl = pm + parts * 32;
   AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, n_heads / n_kv_heads,
-             s_pool, bpwg, nsplit_max, qg_max, B * n_kv_heads * nsplit_max,
-             scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
-  const int members = n_heads / n_kv_heads * qg_max;
-  dim3 grid((B * n_kv_heads * nsplit_max + 7) / 8 * 8 * members);
+             s_pool, bpwg, nsplit_max, qg_max, B * qg_max * n_kv_heads * nsplit_max, items,
+             items + (size_t)B * qg_max * 8, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
+  const int group = n_heads / n_kv_heads;
+  dim3 grid((B * qg_max * n_kv_heads * nsplit_max + 7) / 8 * 8 * group);
   const int ks = ATTN_WAVES / ntw;
   size_t lds = (size_t)ntw * (dh / 32) * (ks - 1) * 16 * 64 * sizeof(float);  // parts handed over
   {

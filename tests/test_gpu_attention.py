@@ -141,6 +141,42 @@ def test_bf16_launch_shapes_give_the_same_answer():
         b.trj_set_tunable("attn_min_bpw", 2)
 
 
+def test_more_sequences_than_one_pass_of_the_work_list():
+    """1100 short sequences: the list of (sequence, query group) items that shapes the bf16
+    launch is built in passes of 1024 sequences, here in two; a malformed tree in each pass
+    is left out of it."""
+    H, dh = 2, 128
+    rng = np.random.default_rng(9)
+    base = [case(400 + i, H, dh, int(rng.integers(0, 40)), int(rng.integers(1, 6)), "bf16") for i in range(12)]
+    want = [O.tree_attention(*c) for c in base]
+    bad = case(2, H, dh, 10, 5, "bf16", parent=np.array([-1, 0, 2, 1, 0], np.int32))
+    cases = [base[i % 12] for i in range(1100)]
+    cases[500] = cases[1050] = bad
+    got = run_attention("bf16", H, dh, cases, align=32)
+    for i, g in enumerate(got):
+        if i in (500, 1050):
+            assert (g == 0).all()
+        else:
+            assert rel_err(g, want[i % 12]) <= 1e-2, i
+
+
+def test_packed_batch_with_splits_ties_and_both_query_groups():
+    """Sequences of equal length (ties in the longest-first order), trees of more and of
+    fewer than 64 nodes side by side, and a launch shape that splits every key range."""
+    H, dh = 2, 128
+    shapes = [(300, 128), (364, 64), (300, 128), (427, 1), (100, 65), (364, 64)]
+    cases = [case(500 + i, H, dh, L, n, "bf16") for i, (L, n) in enumerate(shapes)]
+    try:
+        b.trj_set_tunable("attn_target_wgs", 4096)
+        b.trj_set_tunable("attn_min_bpw", 1)
+        got = run_attention("bf16", H, dh, cases, align=32)
+    finally:
+        b.trj_set_tunable("attn_target_wgs", 256)
+        b.trj_set_tunable("attn_min_bpw", 2)
+    for g, c in zip(got, cases):
+        assert rel_err(g, O.tree_attention(*c)) <= 1e-2
+
+
 def test_malformed_sequence_is_skipped():
     H, dh = 2, 128
     good = case(1, H, dh, 40, 20, "bf16")
