@@ -52,7 +52,7 @@ struct TreeWs {
   uint64_t* anc;
   float* attn;     // bf16 attention partials
   int32_t* items;  // bf16 attention work items and their count
-  int attn_rows, attn_qg;  // rows per item, items per sequence at most
+  int attn_rows, attn_qg, attn_bpwg, attn_ns;  // the attention launch plan
 };
 struct StepWs {
   TreeWs t;
@@ -75,14 +75,16 @@ static void carve_tree(Carver& c, int dtype, int B, int T, int H, int dh, int ma
   w->anc = c.take<uint64_t>(2 * (size_t)T);
   w->attn = nullptr;
   w->items = nullptr;
-  w->attn_rows = w->attn_qg = 0;
+  w->attn_rows = w->attn_qg = w->attn_bpwg = w->attn_ns = 0;
   if (dtype == TRJ_BF16) {
     int ntw, qg, bpwg, ns;
     attn_bf16_plan(B, T, H, max_seq_slots, &ntw, &qg, &bpwg, &ns);
     w->attn = c.take<float>(attn_bf16_ws_floats(B, qg * ntw, H, dh, ns));
-    w->items = c.take<int32_t>(ATTN_ITEM_WORDS(B, qg));
+    w->items = c.take<int32_t>(ATTN_ITEM_WORDS(B, qg, ns));
     w->attn_rows = 32 * ntw;
     w->attn_qg = qg;
+    w->attn_bpwg = bpwg;
+    w->attn_ns = ns;
   }
 }
 
@@ -352,7 +354,8 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   if (dtype == TRJ_BF16) {
     // rows of malformed sequences read as zeros
     TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
-    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, w.status, B, w.attn_rows, w.attn_qg, w.items, st));
+    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, w.status, B, w.attn_rows, w.attn_qg,
+                              w.attn_bpwg, w.attn_ns, w.items, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
                                  (const uint16_t*)v_layer, w.anc, node_off, kv_off, prefix_len,
                                  w.status, w.items, B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, scale,
@@ -467,7 +470,8 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
-    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg, w.t.items, st));
+    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg,
+                              w.t.attn_bpwg, w.t.attn_ns, w.t.items, st));
     // attention output: padding rows and rows of malformed sequences stay zero all step
     TRJ_TRY(launch_zero_bytes(w.op, (size_t)tp * hd * 2, st));
     { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,

@@ -38,13 +38,13 @@ struct AttnArgs {
   const int32_t* prefix_len;
   const int32_t* status_dev;
   int n_heads, group, s_pool, bpwg, nsplit_max, qg_max;  // group = query heads per K/V head
-  int n_kv_groups;  // items x K/V heads x splits: sets of workgroups that share K/V blocks
-  // work items (sequence, query group) that exist, longest sequence first, and their number
+  int n_kv_groups;  // items x K/V heads: sets of workgroups that share K/V blocks
+  // work items (sequence, key split, query group) that exist, longest sequence first, and their number
   // (written by the prep kernels): workgroups past the list's end leave at once, and they
   // are the LAST ids of the launch, so the live ones spread evenly over the compute units
   // One record of 8 words per item: sequence, query group, first row, rows, prefix
-  // length, first K/V block of the sequence; a workgroup needs nothing else from memory to
-  // find its work, and reads record and count together.
+  // length, first K/V block of the sequence, key split; a workgroup needs nothing else
+  // from memory to find its work, and reads record and count together.
   const int32_t* items;
   const int32_t* n_items;
   float scale_log2e;
@@ -159,16 +159,17 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   // Workgroup ids go round-robin over the 8 dies (XCDs), each with its own L2.  The
   // workgroups that walk the SAME K/V blocks (with grouped-query attention the query heads
   // of a K/V head) get ids that fall on one die, next to each other in its dispatch order,
-  // so that the blocks come from HBM once; the query groups of one sequence are
-  // neighbours in the item list, which puts them n_kv * nsplit_max ids apart on the same
-  // die whenever that product is a multiple of 8.
+  // so that the blocks come from HBM once; the query groups of one (sequence, split) are
+  // neighbours in the item list, which puts them n_kv ids apart on the same die whenever
+  // the number of K/V heads is a multiple of 8.
   const int slot = blockIdx.x >> 3, kvg = (slot / a.group) * 8 + (blockIdx.x & 7);
   if (kvg >= a.n_kv_groups) return;  // padding to a multiple of 8 (uniform)
-  const int sp = kvg % a.nsplit_max, n_kv = a.n_heads / a.group;
-  const int head = ((kvg / a.nsplit_max) % n_kv) * a.group + slot % a.group;
-  const int item = kvg / (a.nsplit_max * n_kv);
+  const int n_kv = a.n_heads / a.group;
+  const int head = (kvg % n_kv) * a.group + slot % a.group;
+  const int item = kvg / n_kv;
   const int32_t* rec = a.items + (size_t)item * 8;  // inside the list's memory for every id
   const int s = rec[0], qg = rec[1], r0 = rec[2], n = rec[3], L = rec[4], blk_base = rec[5];
+  const int sp = rec[6];
   if (item >= a.n_items[0]) return;  // uniform over the workgroup, before any barrier
   const int total = L + n;
   const int nb = (total + 31) >> 5;
@@ -454,8 +455,8 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   float* pm = ws + parts * (dh / 32 * 1024);
   float* pl = pm + parts * 32;
   AttnArgs a{q, k_layer, v_layer, anc, node_off, kv_off, prefix_len, status_dev, n_heads, n_heads / n_kv_heads,
-             s_pool, bpwg, nsplit_max, qg_max, B * qg_max * n_kv_heads * nsplit_max, items,
-             items + (size_t)B * qg_max * 8, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
+             s_pool, bpwg, nsplit_max, qg_max, B * qg_max * nsplit_max * n_kv_heads, items,
+             items + (size_t)B * qg_max * nsplit_max * 8, scale * 1.4426950408889634f, po, pm, pl, tiles_per_seq, out, tiled, tp};
   const int group = n_heads / n_kv_heads;
   dim3 grid((B * qg_max * n_kv_heads * nsplit_max + 7) / 8 * 8 * group);
   const int ks = ATTN_WAVES / ntw;

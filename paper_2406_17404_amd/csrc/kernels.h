@@ -36,15 +36,15 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
                      const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
                      int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
                      int32_t* row_seq, hipStream_t st);
-// List of the (sequence, query group) pairs that exist, for the bf16 attention launch:
-// n records of 8 words {sequence, group, first row, rows, prefix length, kv_off / 32, 0, 0},
-// sequences ordered by length (prefix + tree), longest first, when B <= 1024 (else in
-// index order); word 8 * B * qg_max holds n.  Sequences whose status is not 0 are left
-// out.  Must follow launch_tree_prep on the stream.  ATTN_ITEM_WORDS(B, qg_max) words.
-#define ATTN_ITEM_WORDS(B, qg_max) ((size_t)(B) * (qg_max) * 8 + 8)
+// List of the (sequence, key split, query group) triples that exist, for the bf16 attention
+// launch: n records of 8 words {sequence, group, first row, rows, prefix length,
+// kv_off / 32, split, 0}, sequences ordered by length (prefix + tree), longest first, when
+// B <= 1024 (else in index order); word 8 * B * qg_max * nsplit_max holds n.  Sequences
+// whose status is not 0 are left out.  Must follow launch_tree_prep on the stream.
+#define ATTN_ITEM_WORDS(B, qg_max, nsplit_max) ((size_t)(B) * (qg_max) * (nsplit_max) * 8 + 8)
 int launch_attn_items(const int32_t* node_off, const int32_t* prefix_len, const int32_t* kv_off,
                       const int32_t* status_dev, int B, int rows_per_item, int qg_max,
-                      int32_t* items, hipStream_t st);
+                      int blocks_per_item, int nsplit_max, int32_t* items, hipStream_t st);
 int launch_argmax(const float* logits, int T, int V, int32_t* out, hipStream_t st);
 int launch_accept(const int32_t* argmax, const int32_t* tok, const int32_t* parent,
                   const int32_t* node_off, const int32_t* status_in, int B, int T,

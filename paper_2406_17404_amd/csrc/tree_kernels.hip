@@ -88,14 +88,16 @@ __global__ void prep_clear_kernel(int32_t* depth, int32_t* anc_words, int32_t* r
 }
 
 // One workgroup of 1024 threads builds the attention launch's item list.  Chunks of 1024
-// sequences: thread i owns sequence base + i, counts its query groups (0 when its status
-// is not 0), and an inclusive scan over the chunk gives every sequence its place.  With one
+// sequences: thread i owns sequence base + i, counts its items (query groups x key splits
+// of blocks_per_item 32-slot blocks; 0 when its status is not 0), and an inclusive scan
+// over the chunk gives every sequence its place.  With one
 // chunk (B <= 1024) the sequences are first ranked by length, longest first (ties by
 // index), so that the long ones start early and the launch ends evenly.
 __global__ __launch_bounds__(1024) void attn_items_kernel(
     const int32_t* __restrict__ node_off, const int32_t* __restrict__ prefix_len,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ status, int B,
-    int rows_per_item, int qg_max, int32_t* __restrict__ items) {
+    int rows_per_item, int qg_max, int blocks_per_item, int nsplit_max,
+    int32_t* __restrict__ items) {
   __shared__ int32_t key[1024], cnt[1024], scan[1024];
   const int tid = threadIdx.x;
   int carry = 0;
@@ -106,8 +108,11 @@ __global__ __launch_bounds__(1024) void attn_items_kernel(
       n = node_off[s + 1] - node_off[s];
       len = prefix_len[s] + n;
     }
-    int nq = (n + rows_per_item - 1) / rows_per_item;
-    if (nq > qg_max) nq = qg_max;
+    int ng = (n + rows_per_item - 1) / rows_per_item;
+    if (ng > qg_max) ng = qg_max;
+    int nsp = (((len + 31) >> 5) + blocks_per_item - 1) / blocks_per_item;
+    if (nsp > nsplit_max) nsp = nsplit_max;
+    const int nq = len < 0 ? 0 : ng * nsp;
     int place = tid;  // position of this sequence within the chunk
     if (B <= 1024) {
       key[tid] = len;
@@ -129,29 +134,30 @@ __global__ __launch_bounds__(1024) void attn_items_kernel(
     }
     if (s < B) {
       const int at = carry + scan[place] - nq;
-      for (int g = 0; g < nq; ++g) {
-        int32_t* rec = items + (size_t)(at + g) * 8;
+      for (int j = 0; j < nq; ++j) {  // the query groups of a split next to each other
+        int32_t* rec = items + (size_t)(at + j) * 8;
         rec[0] = s;
-        rec[1] = g;
+        rec[1] = j % ng;
         rec[2] = node_off[s];
         rec[3] = n;
         rec[4] = len - n;
         rec[5] = kv_off[s] >> 5;
-        rec[6] = rec[7] = 0;
+        rec[6] = j / ng;
+        rec[7] = 0;
       }
     }
     carry += scan[1023];
     __syncthreads();
   }
-  if (tid == 0) items[(size_t)B * qg_max * 8] = carry;
+  if (tid == 0) items[(size_t)B * qg_max * nsplit_max * 8] = carry;
 }
 
 int launch_attn_items(const int32_t* node_off, const int32_t* prefix_len, const int32_t* kv_off,
                       const int32_t* status_dev, int B, int rows_per_item, int qg_max,
-                      int32_t* items, hipStream_t st) {
-  if (qg_max < 1 || rows_per_item < 1) return TRJ_ERR_BAD_SHAPE;
+                      int blocks_per_item, int nsplit_max, int32_t* items, hipStream_t st) {
+  if (qg_max < 1 || rows_per_item < 1 || blocks_per_item < 1 || nsplit_max < 1) return TRJ_ERR_BAD_SHAPE;
   attn_items_kernel<<<1, 1024, 0, st>>>(node_off, prefix_len, kv_off, status_dev, B, rows_per_item,
-                                        qg_max, items);
+                                        qg_max, blocks_per_item, nsplit_max, items);
   return check_launch();
 }
 
