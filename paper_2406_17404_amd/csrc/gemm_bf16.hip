@@ -437,7 +437,7 @@ static void launch_t(const uint16_t* xp, const uint16_t* w, int tp, int n_in, in
 // (about 700 x 16 KiB saturate HBM here), with as many rows per workgroup as that allows,
 // because a workgroup re-reads the whole activation slice for its rows.
 struct GemmPlan {
-  int mt, rt, kw, ph, split_k;
+  int mt, rt, kw, wt, ph, split_k;
   bool big;
 };
 static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
@@ -453,8 +453,21 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   };
   // many token rows: wavefronts that own two row tiles (see gemm_t_kernel), if that still
   // gives the launch enough workgroups
+  // many-rows kernel: 2 or 4 row tiles per wavefront.  Four halve the LDS reads per matrix
+  // instruction but leave one workgroup per compute unit, so they pay off only when the
+  // launch's last round of 256 workgroups is well filled (measured at 1024 token rows:
+  // faster by 5-10 % for 12288, 16384, 28672, 32000, 65536 output rows, slower by 10 % for
+  // 22016, where the last round is a third full); split-k launches stay with two.
+  g.wt = 2;
+  if (g_tune.gemm_big_wt == 4) g.wt = 4;
+  else if (g_tune.gemm_big_wt == 0 && split_k == 1) {
+    const long wgs4 = (long)((ntiles + 15) / 16) * tblocks;
+    const long last = wgs4 % 256;
+    if (wgs4 >= 128 && (last == 0 || last >= 154)) g.wt = 4;
+  }
+  const int rgt = 4 * g.wt;  // row tiles per workgroup of the many-rows kernel
   g.big = g.mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t &&
-          (long)((ntiles + 7) / 8) * tblocks * splits(BIG_PH) >= 128;
+          (long)((ntiles + rgt - 1) / rgt) * tblocks * splits(BIG_PH) >= 128;
   g.ph = g.big ? BIG_PH : (g.mt == 4 ? 16 : 32);
   g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2)
@@ -481,7 +494,8 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
     else if (g.kw == 4) launch_p<M, 2, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);  \
     else launch_p<M, 2, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);                 \
   } while (0)
-  if (g.big) launch_t<4, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
+  if (g.big && g.wt == 4) launch_t<4, 4, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
+  else if (g.big) launch_t<4, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
   else if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else TRJ_P(4);
 #undef TRJ_P
   return check_launch();

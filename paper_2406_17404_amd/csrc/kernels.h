@@ -11,6 +11,7 @@ struct Tunables {
   int gemm_cfg = 0;            // 0: choose the workgroup shape per GEMM; 1..4 force one
   int gemm_big_t = 256;        // padded token rows from which wavefronts own two row tiles (0: never)
   int attn_target_wgs = 256;   // attention workgroups per launch aimed at (one per CU)
+  int gemm_big_wt = 0;         // row tiles per wavefront of the many-rows kernel (2, 4; 0 = choose)
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
 extern Tunables g_tune;

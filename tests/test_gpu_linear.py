@@ -42,6 +42,20 @@ def test_bf16_linear(T, n_in, n_out, split_k):
     assert rel_err(got, want) <= 1e-5
 
 
+@pytest.mark.parametrize("T,n_in,n_out,wt", [
+    (1024, 528, 4128, 4),    # 129 row tiles: the last workgroup of 16 holds one
+    (512, 2064, 8192, 4), (300, 1024, 6176, 4), (512, 2064, 8192, 2),
+    (1024, 256, 16384, 0)])  # 0: the plan itself picks four row tiles per wavefront here
+def test_bf16_linear_many_rows_tiles_per_wavefront(T, n_in, n_out, wt):
+    try:
+        b.trj_set_tunable("gemm_big_wt", wt)
+        got, want = run_linear("bf16", T, n_in, n_out, 1)
+    finally:
+        b.trj_set_tunable("gemm_big_wt", 0)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= 1e-5
+
+
 @pytest.mark.parametrize("T,n_in,n_out", [(15, 256, 768), (3, 1024, 64), (64, 48, 2048)])
 def test_f32_linear(T, n_in, n_out):
     got, want = run_linear("f32", T, n_in, n_out, 0)
