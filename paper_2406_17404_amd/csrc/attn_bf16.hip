@@ -20,6 +20,8 @@
 // row in split order.  (Merging inside the same launch by "last workgroup to arrive"
 // needs device-scope fences; on this multi-die part each of them writes back and
 // invalidates a whole L2, which measured 3-4x the cost of the separate launch.)
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -146,7 +148,7 @@ __device__ inline void attn_store_row(const AttnArgs& a, int t, int head, int c,
   *reinterpret_cast<u32x2*>(dst) = v;
 }
 
-template <int DH, int NTW>
+template <int DH, int NTW, bool XCHG>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArgs a) {
   constexpr int KS = ATTN_WAVES / NTW, KSTEPS = DH / 16, MTV = DH / 32;
   constexpr int OW = MTV * 16 * 64;  // floats of one wavefront's O tile
@@ -206,67 +208,121 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void tree_attn_bf16_kernel(AttnArg
   const size_t plane = (size_t)(head / a.group) * a.s_pool * DH;  // the group's K/V head
   const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_layer + plane) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_layer + plane) + lane;
-  u32x4 kreg[KSTEPS], vreg[MTV][2];
-  auto load_k = [&](int b) {
-    const u32x4* kb = kp + (size_t)(blk_base + b) * KSTEPS * 64;
-#pragma unroll
-    for (int k = 0; k < KSTEPS; ++k) kreg[k] = kb[k * 64];
-  };
-  auto load_v = [&](int b) {
-    const u32x4* vb = vp + (size_t)(blk_base + b) * MTV * 2 * 64;
-#pragma unroll
-    for (int mt = 0; mt < MTV; ++mt)
-#pragma unroll
-      for (int kg = 0; kg < 2; ++kg) vreg[mt][kg] = vb[(mt * 2 + kg) * 64];
-  };
+  u32x4 kreg[KSTEPS], vreg[2 * MTV];  // 1-KiB pieces of a block; V piece mt * 2 + kg
+  if (!valid) anc0 = anc1 = 0;        // a row that does not exist sees no tree node
 
-  int b = b0 + ks;
-  if (b < b1) {
-    load_k(b);
-    load_v(b);
-  }
-  if (!valid) anc0 = anc1 = 0;  // a row that does not exist sees no tree node
-  for (; b < b1; b += KS) {
-    const int key0 = b * 32;
-    const bool need_mask = key0 + 32 > L;
-    f32x16 sacc;
+  // The walk over the blocks, compiled once per (HALF, STREAM).
+  // NTW == 2: the two wavefronts of a key stream need the same K/V block (one per query
+  // tile).  Each loads HALF of its pieces from memory and hands them to the other through
+  // LDS (two buffers, one LDS barrier per block; every wavefront makes the same number of
+  // trips, one that has run out of blocks reloads its last one and skips the arithmetic),
+  // so every byte is asked for once.  (Handing K over before the first product and V
+  // before the second, with a barrier each, measured slower at every length.)
+  // STREAM: no other workgroup reads these blocks (one query group, one query head per K/V
+  // head), so the loads carry the streaming hint; with a second reader shortly after
+  // (through L2, or the other wavefront of the pair before the exchange existed) the hint
+  // costs a second trip to HBM.
+  auto run = [&](auto half_c, auto stream_c) {
+    constexpr int HALF = decltype(half_c)::value;
+    constexpr bool STREAM = decltype(stream_c)::value;
+    constexpr bool PAIR = NTW == 2 && XCHG;
+    constexpr int KN = PAIR ? KSTEPS / 2 : KSTEPS, K0 = PAIR ? HALF * KN : 0;
+    constexpr int VN = PAIR ? MTV : 2 * MTV, V0 = PAIR ? HALF * VN : 0;
+    auto ldg = [&](const u32x4* p) -> u32x4 {
+      if constexpr (STREAM) return __builtin_nontemporal_load(p);
+      else return *p;
+    };
+    auto load_k = [&](int blk) {
+      const u32x4* kb = kp + (size_t)(blk_base + blk) * KSTEPS * 64;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+      for (int k = 0; k < KN; ++k) kreg[K0 + k] = ldg(kb + (K0 + k) * 64);
+    };
+    auto load_v = [&](int blk) {
+      const u32x4* vb = vp + (size_t)(blk_base + blk) * MTV * 2 * 64;
 #pragma unroll
-    for (int k = 0; k < KSTEPS; ++k)
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[k]), qreg[k],
-                                                     sacc, 0, 0, 0);
-    const int bn = b + KS;
-    if (bn < b1) load_k(bn);  // uniform branch; in flight during the softmax and P*V
-
-    if (key0 + 32 > total) {
-      // slots past the sequence's last row may hold anything (NaN bit patterns too):
-      // clear them in the V operand, their probabilities are exactly zero
-#pragma unroll
-      for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          int key = key0 + 16 * kg + 4 * hh + 8 * (e >> 2) + (e & 3);
-          if (key >= total) {
-            uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
-#pragma unroll
-            for (int mt = 0; mt < MTV; ++mt) vreg[mt][kg][e >> 1] &= keep;
-          }
-        }
+      for (int i = 0; i < VN; ++i) vreg[V0 + i] = ldg(vb + (V0 + i) * 64);
+    };
+    u32x4* xch = reinterpret_cast<u32x4*>(red);  // [2 buffers][KS][2 halves][KN + VN][64]
+    const int iters = (b1 - b0 + KS - 1) / KS;   // the same for every wavefront
+    int b = b0 + ks;
+    if (PAIR || b < b1) {
+      load_k(min(b, b1 - 1));
+      load_v(min(b, b1 - 1));
     }
-    float alpha;
-    u32x4 pk[2];
-    if (need_mask) softmax_tile_tree(sacc, key0, hh, L, anc0, anc1, a.scale_log2e, m, l, alpha, pk);
-    else softmax_tile_prefix(sacc, a.scale_log2e, m, l, alpha, pk);
-    rescale_o<MTV>(o, alpha);
+    for (int it = 0; it < iters; ++it, b += KS) {
+      const bool live = b < b1;  // the same for both wavefronts of a stream
+      if constexpr (PAIR) {
+        constexpr int KO = (HALF ^ 1) * KN, VO = (HALF ^ 1) * VN;
+        u32x4* mine = xch + (size_t)((((it & 1) * KS + ks) * 2 + HALF) * (KN + VN)) * 64 + lane;
+        const u32x4* theirs =
+            xch + (size_t)((((it & 1) * KS + ks) * 2 + (HALF ^ 1)) * (KN + VN)) * 64 + lane;
 #pragma unroll
-    for (int mt = 0; mt < MTV; ++mt)
+        for (int k = 0; k < KN; ++k) mine[k * 64] = kreg[K0 + k];
 #pragma unroll
-      for (int kg = 0; kg < 2; ++kg)
-        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[mt][kg]),
-                                                        __builtin_bit_cast(bf16x8, pk[kg]), o[mt],
-                                                        0, 0, 0);
-    if (bn < b1) load_v(bn);  // in flight during the next S^T and softmax
+        for (int i = 0; i < VN; ++i) mine[(KN + i) * 64] = vreg[V0 + i];
+        lds_barrier();
+#pragma unroll
+        for (int k = 0; k < KN; ++k) kreg[KO + k] = theirs[k * 64];
+#pragma unroll
+        for (int i = 0; i < VN; ++i) vreg[VO + i] = theirs[(KN + i) * 64];
+      }
+      const bool more = PAIR ? it + 1 < iters : b + KS < b1;
+      const int bn = min(b + KS, b1 - 1);
+      const int key0 = b * 32;
+      f32x16 sacc;
+      if (live) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+        for (int k = 0; k < KSTEPS; ++k)
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[k]),
+                                                         qreg[k], sacc, 0, 0, 0);
+      }
+      if (more) load_k(bn);  // uniform branch; in flight during the softmax and P*V
+      if (live) {
+        if (key0 + 32 > total) {
+          // slots past the sequence's last row may hold anything (NaN bit patterns too):
+          // clear them in the V operand, their probabilities are exactly zero
+#pragma unroll
+          for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              int key = key0 + 16 * kg + 4 * hh + 8 * (e >> 2) + (e & 3);
+              if (key >= total) {
+                uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
+#pragma unroll
+                for (int mt = 0; mt < MTV; ++mt) vreg[mt * 2 + kg][e >> 1] &= keep;
+              }
+            }
+        }
+        float alpha;
+        u32x4 pk[2];
+        if (key0 + 32 > L)
+          softmax_tile_tree(sacc, key0, hh, L, anc0, anc1, a.scale_log2e, m, l, alpha, pk);
+        else
+          softmax_tile_prefix(sacc, a.scale_log2e, m, l, alpha, pk);
+        rescale_o<MTV>(o, alpha);
+#pragma unroll
+        for (int mt = 0; mt < MTV; ++mt)
+#pragma unroll
+          for (int kg = 0; kg < 2; ++kg)
+            o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, vreg[mt * 2 + kg]), __builtin_bit_cast(bf16x8, pk[kg]),
+                o[mt], 0, 0, 0);
+      }
+      if (more) load_v(bn);  // in flight during the next S^T and softmax
+    }
+  };
+  {
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    // uniform over the workgroup; two wavefronts that load the same block rule it out too
+    const bool stream = (NTW == 1 || XCHG) && a.group == 1 && rec[7] == 0;
+    if (NTW == 2 && XCHG && nt == 1) {
+      if (stream) run(I1{}, std::true_type{}); else run(I1{}, std::false_type{});
+    } else {
+      if (stream) run(I0{}, std::true_type{}); else run(I0{}, std::false_type{});
+    }
   }
 
   // ---- merge the KS key streams of every query tile (fixed order, deterministic)
@@ -461,20 +517,37 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   dim3 grid((B * qg_max * n_kv_heads * nsplit_max + 7) / 8 * 8 * group);
   const int ks = ATTN_WAVES / ntw;
   size_t lds = (size_t)ntw * (dh / 32) * (ks - 1) * 16 * 64 * sizeof(float);  // parts handed over
+  // With two query tiles per workgroup the wavefront pairs either both load every block, or
+  // split the loads and exchange halves through LDS.  The exchange costs a barrier per block
+  // and pays once a wavefront walks enough blocks (measured: 2 blocks per wavefront 13.2
+  // against 12 us, 8: 33.9 against 31.9, 20: 119 against 137, 32: 89 against 98).
+  // It is the streaming hint that pays for it, and the hint needs blocks that nobody else
+  // reads: one query head per K/V head, and trees of at most 64 nodes (known here only on
+  // average; a sequence with more runs the exchange without the hint, 3-6 % slower than
+  // the plain pair).
+  const bool xchg = ntw == 2 && bpwg >= g_tune.attn_xchg_min_blocks && n_heads == n_kv_heads &&
+                    T <= 64 * B;
+  if (xchg) {  // 2 buffers x streams x halves x pieces
+    size_t xch = (size_t)2 * ks * 2 * (dh / 32 + dh / 32) * 1024;
+    if (xch > lds) lds = xch;
+  }
   {
     ProfScope ps_(KC_ATTN, st);
-#define TRJ_ATTN(D, Q)                                                                        \
+#define TRJ_ATTN(D, Q, X)                                                                     \
   do {                                                                                        \
     static bool big_lds_allowed = false; /* one-time, per instantiation */                    \
     if (!big_lds_allowed) {                                                                   \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tree_attn_bf16_kernel<D, Q>),   \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tree_attn_bf16_kernel<D, Q, X>), \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);      \
       big_lds_allowed = true;                                                                 \
     }                                                                                         \
-    tree_attn_bf16_kernel<D, Q><<<grid, ATTN_WAVES * 64, lds, st>>>(a);                       \
+    tree_attn_bf16_kernel<D, Q, X><<<grid, ATTN_WAVES * 64, lds, st>>>(a);                    \
   } while (0)
-    if (dh == 128) { if (ntw == 1) TRJ_ATTN(128, 1); else TRJ_ATTN(128, 2); }
-    else { if (ntw == 1) TRJ_ATTN(64, 1); else TRJ_ATTN(64, 2); }
+    if (dh == 128) {
+      if (ntw == 1) TRJ_ATTN(128, 1, false); else if (xchg) TRJ_ATTN(128, 2, true); else TRJ_ATTN(128, 2, false);
+    } else {
+      if (ntw == 1) TRJ_ATTN(64, 1, false); else if (xchg) TRJ_ATTN(64, 2, true); else TRJ_ATTN(64, 2, false);
+    }
 #undef TRJ_ATTN
   }
   int rc = check_launch();

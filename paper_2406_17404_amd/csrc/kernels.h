@@ -12,6 +12,7 @@ struct Tunables {
   int gemm_big_t = 256;        // padded token rows from which wavefronts own two row tiles (0: never)
   int attn_target_wgs = 256;   // attention workgroups per launch aimed at (one per CU)
   int gemm_big_wt = 0;         // row tiles per wavefront of the many-rows kernel (2, 4; 0 = choose)
+  int attn_xchg_min_blocks = 48;  // blocks per workgroup from which wavefront pairs split their loads
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
 extern Tunables g_tune;
@@ -39,7 +40,7 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
                      int32_t* row_seq, hipStream_t st);
 // List of the (sequence, key split, query group) triples that exist, for the bf16 attention
 // launch: n records of 8 words {sequence, group, first row, rows, prefix length,
-// kv_off / 32, split, 0}, sequences ordered by length (prefix + tree), longest first, when
+// kv_off / 32, split, 1 if the sequence has more than one group}, sequences ordered by length (prefix + tree), longest first, when
 // B <= 1024 (else in index order); word 8 * B * qg_max * nsplit_max holds n.  Sequences
 // whose status is not 0 are left out.  Must follow launch_tree_prep on the stream.
 #define ATTN_ITEM_WORDS(B, qg_max, nsplit_max) ((size_t)(B) * (qg_max) * (nsplit_max) * 8 + 8)

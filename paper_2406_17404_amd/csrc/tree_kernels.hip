@@ -143,7 +143,7 @@ __global__ __launch_bounds__(1024) void attn_items_kernel(
         rec[4] = len - n;
         rec[5] = kv_off[s] >> 5;
         rec[6] = j / ng;
-        rec[7] = 0;
+        rec[7] = ng > 1;  // another query group of the sequence reads the same blocks
       }
     }
     carry += scan[1023];

@@ -177,6 +177,54 @@ def test_packed_batch_with_splits_ties_and_both_query_groups():
         assert rel_err(g, O.tree_attention(*c)) <= 1e-2
 
 
+@pytest.fixture
+def pair_exchange():
+    """Launch shape in which the two wavefronts of a key stream split the loads of every
+    K/V block and hand halves to each other (normally chosen only for long prefixes)."""
+    b.trj_set_tunable("attn_xchg_min_blocks", 1)
+    yield
+    b.trj_set_tunable("attn_xchg_min_blocks", 48)
+
+
+@pytest.mark.parametrize("H,dh,L,n,wgs", [
+    (2, 128, 0, 64, 256), (3, 128, 31, 33, 256), (2, 128, 300, 64, 256), (2, 64, 257, 50, 256),
+    (2, 128, 1500, 64, 1),       # one workgroup per head: 49 blocks over 4 streams, uneven
+    (1, 128, 1500, 64, 4096),    # many splits: some streams of a workgroup have no block at all
+    (2, 64, 777, 64, 64)])
+def test_pair_exchange_single_sequence(pair_exchange, H, dh, L, n, wgs):
+    c = case(13 * L + n, H, dh, L, n, "bf16")
+    try:
+        b.trj_set_tunable("attn_target_wgs", wgs)
+        b.trj_set_tunable("attn_min_bpw", 1)
+        got = run_attention("bf16", H, dh, [c])[0]
+    finally:
+        b.trj_set_tunable("attn_target_wgs", 256)
+        b.trj_set_tunable("attn_min_bpw", 2)
+    assert np.isfinite(got).all()
+    assert rel_err(got, O.tree_attention(*c)) <= 1e-2
+
+
+def test_pair_exchange_packed_batch_cold_and_warm(pair_exchange):
+    """Ragged packed batch through the exchange path, one tree with more than 64 nodes
+    among them (its two query groups share blocks, so its loads carry no streaming hint);
+    repeated with cache-emptying writes in between: every launch gives the same rows."""
+    H, dh = 4, 128
+    shapes = [(700, 100), (33, 20), (450, 64), (0, 10), (129, 33), (900, 5)]
+    cases = [case(600 + i, H, dh, L, n, "bf16") for i, (L, n) in enumerate(shapes)]
+    want = [O.tree_attention(*c) for c in cases]
+    first = None
+    for trial in range(12):
+        if trial % 3 == 0:
+            torch.randn(64 * 1024 * 1024, device=DEV)
+        got = run_attention("bf16", H, dh, cases, align=32)
+        for g, w in zip(got, want):
+            assert rel_err(g, w) <= 1e-2, trial
+        if first is None:
+            first = got
+        else:
+            assert all(np.array_equal(a, c) for a, c in zip(first, got)), trial
+
+
 def test_malformed_sequence_is_skipped():
     H, dh = 2, 128
     good = case(1, H, dh, 40, 20, "bf16")
