@@ -350,13 +350,13 @@ def main():
                            "not a throughput claim (random-init weights)"}
         step()  # leave the pools as the timed steps left them
 
-    # ---- the standalone tree-attention entry point at the sweep sizes (prefix 512..32k, random
+    # ---- the standalone tree-attention entry point at the sweep sizes (prefix 512..128k, random
     # trees of 16..128 nodes, 32 heads x 128), layers rotated so that no launch finds its K/V in a cache
     attn_sweep = None
     if B == 1 and not args.no_extras:
         attn_sweep = []
         for Ls, Ns in ((512, 16), (512, 64), (512, 128), (2048, 16), (2048, 64), (2048, 128),
-                       (8192, 16), (8192, 64), (8192, 128), (32768, 64)):
+                       (8192, 16), (8192, 64), (8192, 128), (32768, 64), (131072, 64)):
             sp = (Ls + Ns + 63) // 64 * 64
             n_rot = max(4, min(32, int(3e9 // (2 * H * sp * dh * 2))))   # > 1 GB of distinct K/V
             qd = torch.randn(Ns, H, dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -373,18 +373,27 @@ def main():
                                      Ls + Ns, b.BF16, float(1.0 / np.sqrt(dh)), ws_s, out_s)
             run_all()
             torch.cuda.synchronize()
-            t_us = {}
-            for name in ("tree_attn", "attn_combine"):
-                b.trj_profile_begin(b.KERNEL_CLASSES[name], 2 * n_rot)
+            # three event timings per launch pair: S around the attention kernel, C around
+            # the merge kernel, A from the start of the first to the end of the second; each
+            # holds the cost of one event pair, so attention = A - C, merge = A - S
+            def timed(first, last):
+                b.trj_profile_begin_span(b.KERNEL_CLASSES[first], b.KERNEL_CLASSES[last], 2 * n_rot)
                 run_all()
                 torch.cuda.synchronize()
                 ts = b.trj_profile_end(2 * n_rot)
-                t_us[name] = 1e3 * sum(ts) / max(len(ts), 1)
+                return 1e3 * sum(ts) / max(len(ts), 1), len(ts)
+            t_s, _ = timed("tree_attn", "tree_attn")
+            t_c, n_c = timed("attn_combine", "attn_combine")
+            if n_c:
+                t_a, _ = timed("tree_attn", "attn_combine")
+                attn_us, merge_us = t_a - t_c, t_a - t_s
+            else:   # one workgroup per head saw every key: no merge launch, no follower to difference with
+                attn_us, merge_us = t_s, 0.0
             by = attn_bytes(Ls, Ns, H, dh)
-            tot = t_us["tree_attn"] + t_us["attn_combine"]
-            attn_sweep.append({"prefix_len": Ls, "tree_nodes": Ns, "attn_us": round(t_us["tree_attn"], 2),
-                               "merge_us": round(t_us["attn_combine"], 2), "alg_bytes": by,
-                               "GBps": round(by / (tot * 1e-6) / 1e9, 1),
+            tot = attn_us + merge_us
+            attn_sweep.append({"prefix_len": Ls, "tree_nodes": Ns, "attn_us": round(attn_us, 2),
+                               "merge_us": round(merge_us, 2), "bracketed_attn_us": round(t_s, 2),
+                               "alg_bytes": by, "GBps": round(by / (tot * 1e-6) / 1e9, 1),
                                "frac_hbm": round(by / (tot * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)})
             del kps, vps
 
