@@ -121,6 +121,57 @@ def cpu_baseline(wl, n_sample_layers=None):
                       f"measured {t2 - t0:.1f} s, estimated full step {est:.1f} s"}
 
 
+ATTN_SWEEP = ((512, 16), (512, 64), (512, 128), (2048, 16), (2048, 64), (2048, 128),
+              (8192, 16), (8192, 64), (8192, 128), (32768, 64), (131072, 64))
+
+
+def attn_case(b, I, torch, np, H, dh, Ls, Ns, seed):
+    """One size of the tree-attention sweep through the standalone entry point: prefix Ls,
+    a random tree of Ns nodes, H heads; K/V rotated over > 1 GB of distinct layers."""
+    dev = "cuda"
+    i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(dev)
+    desc = b.ModelDesc(1, 64, H, dh, 64, 64, 1e-5, 1e4, b.BF16)
+    sp = (Ls + Ns + 63) // 64 * 64
+    n_rot = max(4, min(32, int(3e9 // (2 * H * sp * dh * 2))))
+    qd = torch.randn(Ns, H, dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    kps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    par_s = i32(I.tree_random(Ns, np.random.default_rng(seed)))
+    off_s, kvo_s, pre_s = i32([0, Ns]), i32([0]), i32([Ls])
+    ws_s = torch.empty(b.trj_workspace_bytes(desc, Ns, 1, Ls + Ns), dtype=torch.uint8, device=dev)
+    out_s = torch.empty(Ns, H, dh, device=dev, dtype=torch.bfloat16)
+
+    def run_all():
+        for l in range(n_rot):
+            b.tree_attention(qd, kps[l], vps[l], par_s, off_s, kvo_s, pre_s, 1, Ns, H, dh, sp,
+                             Ls + Ns, b.BF16, float(1.0 / np.sqrt(dh)), ws_s, out_s)
+    run_all()
+    torch.cuda.synchronize()
+
+    # three event timings per launch pair: S around the attention kernel, C around the
+    # merge kernel, A from the start of the first to the end of the second; each holds the
+    # cost of one event pair, so attention = A - C, merge = A - S
+    def timed(first, last):
+        b.trj_profile_begin_span(b.KERNEL_CLASSES[first], b.KERNEL_CLASSES[last], 2 * n_rot)
+        run_all()
+        torch.cuda.synchronize()
+        ts = b.trj_profile_end(2 * n_rot)
+        return 1e3 * sum(ts) / max(len(ts), 1), len(ts)
+    t_s, _ = timed("tree_attn", "tree_attn")
+    t_c, n_c = timed("attn_combine", "attn_combine")
+    if n_c:
+        t_a, _ = timed("tree_attn", "attn_combine")
+        attn_us, merge_us = t_a - t_c, t_a - t_s
+    else:   # one workgroup per head saw every key: no merge launch, no follower to difference with
+        attn_us, merge_us = t_s, 0.0
+    by = attn_bytes(Ls, Ns, H, dh)
+    tot = attn_us + merge_us
+    return {"prefix_len": Ls, "tree_nodes": Ns, "attn_us": round(attn_us, 2),
+            "merge_us": round(merge_us, 2), "bracketed_attn_us": round(t_s, 2),
+            "alg_bytes": by, "GBps": round(by / (tot * 1e-6) / 1e9, 1),
+            "frac_hbm": round(by / (tot * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +184,9 @@ def main():
     ap.add_argument("--no-kernel-times", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the chain-length sweep and the decoding-loop leg")
+    ap.add_argument("--attn-case", default=None, metavar="L,N",
+                    help="only one size of the tree-attention sweep (prefix L, N tree nodes, 32 "
+                         "heads x 128): for profiling that kernel alone")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="launch-shape knob for experiments (see trj_set_tunable)")
     args = ap.parse_args()
@@ -151,6 +205,10 @@ def main():
         name, value = kv.split("=")
         b.trj_set_tunable(name, int(value))
     assert torch.cuda.is_available(), "needs a GPU"
+    if args.attn_case:
+        Ls, Ns = (int(v) for v in args.attn_case.split(","))
+        print(json.dumps({"tree_attn_case": attn_case(b, I, torch, np, 32, 128, Ls, Ns, 1001)}))
+        return
     wl = I.workload(args.workload)
     shape = wl.shape
     H, dh, nl = shape.n_heads, shape.head_dim, shape.n_layers
@@ -354,48 +412,7 @@ def main():
     # trees of 16..128 nodes, 32 heads x 128), layers rotated so that no launch finds its K/V in a cache
     attn_sweep = None
     if B == 1 and not args.no_extras:
-        attn_sweep = []
-        for Ls, Ns in ((512, 16), (512, 64), (512, 128), (2048, 16), (2048, 64), (2048, 128),
-                       (8192, 16), (8192, 64), (8192, 128), (32768, 64), (131072, 64)):
-            sp = (Ls + Ns + 63) // 64 * 64
-            n_rot = max(4, min(32, int(3e9 // (2 * H * sp * dh * 2))))   # > 1 GB of distinct K/V
-            qd = torch.randn(Ns, H, dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
-            kps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
-            vps = torch.randn(n_rot, H * sp * dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
-            par_s = i32(I.tree_random(Ns, np.random.default_rng(wl.seed)))
-            off_s, kvo_s, pre_s = i32([0, Ns]), i32([0]), i32([Ls])
-            ws_s = torch.empty(b.trj_workspace_bytes(desc, Ns, 1, Ls + Ns), dtype=torch.uint8, device=dev)
-            out_s = torch.empty(Ns, H, dh, device=dev, dtype=torch.bfloat16)
-
-            def run_all():
-                for l in range(n_rot):
-                    b.tree_attention(qd, kps[l], vps[l], par_s, off_s, kvo_s, pre_s, 1, Ns, H, dh, sp,
-                                     Ls + Ns, b.BF16, float(1.0 / np.sqrt(dh)), ws_s, out_s)
-            run_all()
-            torch.cuda.synchronize()
-            # three event timings per launch pair: S around the attention kernel, C around
-            # the merge kernel, A from the start of the first to the end of the second; each
-            # holds the cost of one event pair, so attention = A - C, merge = A - S
-            def timed(first, last):
-                b.trj_profile_begin_span(b.KERNEL_CLASSES[first], b.KERNEL_CLASSES[last], 2 * n_rot)
-                run_all()
-                torch.cuda.synchronize()
-                ts = b.trj_profile_end(2 * n_rot)
-                return 1e3 * sum(ts) / max(len(ts), 1), len(ts)
-            t_s, _ = timed("tree_attn", "tree_attn")
-            t_c, n_c = timed("attn_combine", "attn_combine")
-            if n_c:
-                t_a, _ = timed("tree_attn", "attn_combine")
-                attn_us, merge_us = t_a - t_c, t_a - t_s
-            else:   # one workgroup per head saw every key: no merge launch, no follower to difference with
-                attn_us, merge_us = t_s, 0.0
-            by = attn_bytes(Ls, Ns, H, dh)
-            tot = attn_us + merge_us
-            attn_sweep.append({"prefix_len": Ls, "tree_nodes": Ns, "attn_us": round(attn_us, 2),
-                               "merge_us": round(merge_us, 2), "bracketed_attn_us": round(t_s, 2),
-                               "alg_bytes": by, "GBps": round(by / (tot * 1e-6) / 1e9, 1),
-                               "frac_hbm": round(by / (tot * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)})
-            del kps, vps
+        attn_sweep = [attn_case(b, I, torch, np, H, dh, Ls, Ns, wl.seed) for Ls, Ns in ATTN_SWEEP]
 
     cpu = None
     if not args.no_cpu_baseline and B == 1:  # the oracle handles one sequence at a time
