@@ -290,9 +290,9 @@ int32_t tr_jacobi_generate_workspace_bytes(const trj_model_desc* desc, int32_t n
 
 /* Greedy generation for ONE sequence whose K/V live at slot 0.. of the pool (kv offset
  * 0; s_pool slots per head, a multiple of TRJ_KV_BLOCK, at least prompt_len +
- * max_new_tokens + N).  The prompt's K/V are computed first by chain-shaped trees of up
- * to TRJ_N_MAX tokens (an ordinary causal forward); the pool's previous contents are
- * ignored.  h_prompt: HOST [prompt_len], prompt_len >= 1, ids in [0, vocab).  Outputs
+ * max_new_tokens + N).  The prompt's K/V are computed first by chain-shaped trees of
+ * TRJ_N_MAX tokens (an ordinary causal forward), up to eight of them packed into one step
+ * as "sequences" that share the K/V region; the pool's previous contents are ignored.  h_prompt: HOST [prompt_len], prompt_len >= 1, ids in [0, vocab).  Outputs
  * (HOST): h_tokens[max_new_tokens], *h_n_tokens, h_accept_hist[max_new_tokens] (accepted
  * drafts per round, may be NULL), *h_n_steps (rounds).  Synchronous: returns after the
  * stream has drained.  Errors as above; nothing is written to the host outputs'

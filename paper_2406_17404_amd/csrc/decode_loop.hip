@@ -115,6 +115,21 @@ struct LoopOut {  // device -> host every round
   int32_t accept_len, best, bonus, new_len, status;
   int32_t pad[3];
 };
+// A prompt pass takes up to PREFILL_CHUNKS chain-shaped trees of TRJ_N_MAX tokens in one
+// packed step: chunk c is a "sequence" with the same K/V region as the others and a prefix
+// that ends where chunk c - 1 ends, so its rows see the K/V that the same layer's QKV
+// launch has just written for the chunks before it.  One pass over the weights then
+// serves 1024 prompt tokens instead of 128.
+constexpr int PREFILL_CHUNKS = 8;
+struct PrefillBlock {  // host -> device every prompt pass
+  int32_t tok[PREFILL_CHUNKS * TRJ_N_MAX];
+  int32_t parent[PREFILL_CHUNKS * TRJ_N_MAX];
+  int32_t node_off[PREFILL_CHUNKS + 1];
+  int32_t kv_off[PREFILL_CHUNKS];
+  int32_t prefix_len[PREFILL_CHUNKS];
+  int32_t status[PREFILL_CHUNKS];
+  int32_t pad[3];
+};
 struct LoopConst {  // host -> device once per tree shape
   int32_t parent[TRJ_N_MAX];
   int32_t node_off[2];
@@ -132,7 +147,7 @@ static int slot_bound(int slots, int s_pool) {
 
 static size_t loop_fixed_bytes() {
   return align_up(sizeof(LoopIn), 256) + align_up(sizeof(LoopOut), 256) +
-         2 * align_up(sizeof(LoopConst), 256);
+         align_up(sizeof(LoopConst), 256) + align_up(sizeof(PrefillBlock), 256);
 }
 
 }  // namespace trj
@@ -187,9 +202,10 @@ int32_t tr_jacobi_generate_workspace_bytes(const trj_model_desc* desc, int32_t n
     int bound = b < s_pool ? b : s_pool;
     size_t a = step_workspace_bytes(*desc, 1, n_nodes, bound);
     need = a > need ? a : need;
-    for (int t : {TRJ_N_MAX, (prompt_len - 1) % TRJ_N_MAX}) {
+    const int full = PREFILL_CHUNKS * TRJ_N_MAX;  // the prompt passes: full ones and the last
+    for (int t : {prompt_len - 1 >= full ? full : 0, (prompt_len - 1) % full}) {
       if (t < 1 || t > bound) continue;
-      a = step_workspace_bytes(*desc, 1, t, bound);
+      a = step_workspace_bytes(*desc, (t + TRJ_N_MAX - 1) / TRJ_N_MAX, t, bound);
       need = a > need ? a : need;
     }
     if (bound >= cap || bound >= s_pool) break;
@@ -226,8 +242,8 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
   base += align_up(sizeof(LoopOut), 256);
   LoopConst* d_tree = reinterpret_cast<LoopConst*>(base);
   base += align_up(sizeof(LoopConst), 256);
-  LoopConst* d_chain = reinterpret_cast<LoopConst*>(base);
-  base += align_up(sizeof(LoopConst), 256);
+  PrefillBlock* d_pf = reinterpret_cast<PrefillBlock*>(base);
+  base += align_up(sizeof(PrefillBlock), 256);
   void* step_ws = base;
   const size_t step_ws_bytes = ws_bytes - loop_fixed_bytes();
 
@@ -238,24 +254,33 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
   *h_n_steps = 0;
 
   // ---- prompt pass: the K/V of prompt[0 .. P-2] through chain-shaped trees (an ordinary
-  // causal forward), TRJ_N_MAX tokens at a time; the last prompt token becomes the root
+  // causal forward), up to PREFILL_CHUNKS x TRJ_N_MAX tokens per packed step; the last
+  // prompt token becomes the root
   int L = 0;
   const int n_ctx0 = prompt_len - 1;
-  for (int i = 0; i < TRJ_N_MAX; ++i) h_c.parent[i] = i - 1;
-  h_c.kv_off = 0;
+  std::vector<PrefillBlock> h_pf_store(1);
+  PrefillBlock& h_pf = h_pf_store[0];
   while (L < n_ctx0) {
-    const int T = n_ctx0 - L < TRJ_N_MAX ? n_ctx0 - L : TRJ_N_MAX;
-    h_c.node_off[0] = 0;
-    h_c.node_off[1] = T;
-    for (int i = 0; i < T; ++i) h_in.tok[i] = h_prompt[L + i];
-    h_in.prefix_len = L;
-    TRJ_HIP(hipMemcpyAsync(d_chain, &h_c, sizeof(h_c), hipMemcpyHostToDevice, st));
-    TRJ_HIP(hipMemcpyAsync(d_in, &h_in, sizeof(h_in), hipMemcpyHostToDevice, st));
-    TRJ_TRY(step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, d_in->tok,
-                      d_chain->parent, d_chain->node_off, &d_chain->kv_off, &d_in->prefix_len, 1, T,
+    const int left = n_ctx0 - L, full = PREFILL_CHUNKS * TRJ_N_MAX;
+    const int T = left < full ? left : full;
+    const int Bc = (T + TRJ_N_MAX - 1) / TRJ_N_MAX;
+    for (int c = 0; c < Bc; ++c) {
+      const int r0 = c * TRJ_N_MAX, n = T - r0 < TRJ_N_MAX ? T - r0 : TRJ_N_MAX;
+      h_pf.node_off[c] = r0;
+      h_pf.kv_off[c] = 0;
+      h_pf.prefix_len[c] = L + r0;
+      for (int i = 0; i < n; ++i) {
+        h_pf.tok[r0 + i] = h_prompt[L + r0 + i];
+        h_pf.parent[r0 + i] = i - 1;
+      }
+    }
+    h_pf.node_off[Bc] = T;
+    TRJ_HIP(hipMemcpyAsync(d_pf, &h_pf, sizeof(h_pf), hipMemcpyHostToDevice, st));
+    TRJ_TRY(step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, d_pf->tok, d_pf->parent,
+                      d_pf->node_off, d_pf->kv_off, d_pf->prefix_len, Bc, T,
                       slot_bound(L + T, s_pool), step_ws, step_ws_bytes, nullptr, nullptr, nullptr,
-                      nullptr, nullptr, nullptr, nullptr, &d_out->status, false, st));
-    // the host blocks are reused by the next pass
+                      nullptr, nullptr, nullptr, nullptr, d_pf->status, false, st));
+    // the host block is reused by the next pass
     TRJ_HIP(hipStreamSynchronize(st));
     L += T;
   }

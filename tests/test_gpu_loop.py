@@ -55,7 +55,9 @@ def gap_at(shape, w, context, t_a, t_b):
 
 @pytest.mark.parametrize("seed,n,r,plen,max_new", [(0, 12, 3, 5, 24), (1, 1, 0, 1, 8), (2, 20, 0, 9, 20),
                                                     (3, 64, 5, 140, 16), (4, 128, 5, 129, 12),
-                                                    (5, 9, 4, 257, 10)])
+                                                    (5, 9, 4, 257, 10),
+                                                    # prompt passes: one packed step of 8 chunks, then 3 chunks
+                                                    (6, 10, 2, 1024 + 300, 6)])
 def test_fp32_loop_equals_oracle_loop_and_autoregressive_greedy(seed, n, r, plen, max_new):
     shape = F32_SHAPE
     w = make_model(shape, seed)
