@@ -42,6 +42,21 @@ def test_bf16_linear(T, n_in, n_out, split_k):
     assert rel_err(got, want) <= 1e-5
 
 
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("T,n_in,n_out,split_k", [(64, 1040, 160, 1), (33, 4096, 6144, 1), (128, 2064, 96, 3),
+                                                  (20, 528, 416, 2)])
+def test_bf16_linear_every_workgroup_shape(cfg, T, n_in, n_out, split_k):
+    """Row tiles x k-parts per workgroup forced to each of the five shapes (row-tile counts
+    that do not divide by the shape's rows, a k-range that ends inside a phase)."""
+    try:
+        b.trj_set_tunable("gemm_cfg", cfg)
+        got, want = run_linear("bf16", T, n_in, n_out, split_k)
+    finally:
+        b.trj_set_tunable("gemm_cfg", 0)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= 1e-5
+
+
 @pytest.mark.parametrize("T,n_in,n_out,wt", [
     (1024, 528, 4128, 4),    # 129 row tiles: the last workgroup of 16 holds one
     (512, 2064, 8192, 4), (300, 1024, 6176, 4), (512, 2064, 8192, 2),
