@@ -475,6 +475,10 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
   // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
   if (shape == 1 && g.mt == 4 && g_tune.gemm_cfg == 0) shape = 4;
+  // 128 token rows, long k-range per workgroup: four k-parts (8 wavefronts) keep twice the
+  // loads in flight per compute unit (QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us; the output
+  // projection's 64 k-steps per split are too short for it, 17.3 against 18.0 us)
+  if (shape == 3 && g_tune.gemm_cfg == 0 && (n_in >> 4) / g.split_k >= 128) shape = 2;
   // few row tiles (the QKV projection of a grouped-query model: 192): one row tile per
   // workgroup and eight k-parts, so that the launch still has a workgroup on most compute
   // units (one compute unit pulls at most ~48 GB/s): 22.8 -> 20.2 us for 6144 x 4096
