@@ -41,8 +41,11 @@ def dev_normal(shape, std, seed):
 
 @pytest.mark.parametrize("name,n_in,n_out", [("qkv", 4096, 12288), ("o", 4096, 4096),
                                              ("gate_up", 4096, 22016), ("down", 11008, 4096),
-                                             ("lm_head", 4096, 32000), ("lm_head_code", 4096, 32256)])
-@pytest.mark.parametrize("T", [64, 128])
+                                             ("lm_head", 4096, 32000), ("lm_head_code", 4096, 32256),
+                                             # the grouped-query 8B shape's projections
+                                             ("qkv_gqa", 4096, 6144), ("gate_up_8b", 4096, 28672),
+                                             ("down_8b", 14336, 4096)])
+@pytest.mark.parametrize("T", [64, 128, 1024])
 def test_projection_shapes_sampled(name, n_in, n_out, T):
     w = dev_normal((n_out, n_in), 0.02, 11)
     x = dev_normal((T, n_in), 1.0, 12)
@@ -87,6 +90,43 @@ def test_attention_sweep_sizes(L, N):
     heads = [0, 13, 31]
     want = O.tree_attention(q[:, heads], k[heads], v[heads], parent, L)
     assert rel_err(got[:, heads], want) <= 1e-2
+
+
+def test_attention_long_prefix_pairs_exchange_halves():
+    """L = 32768, N = 64 at full width: the launch in which the two wavefronts of a key
+    stream split the loads of every block (128 blocks per workgroup) and the loads carry
+    the streaming hint; three heads against the oracle."""
+    test_attention_sweep_sizes(32768, 64)
+
+
+def test_attention_packed_batch_at_full_width():
+    """The packed workload's attention (16 sequences, prefixes 256..4096, 64-node trees,
+    32 heads x 128: one workgroup per sequence and head, longest first, halves exchanged):
+    the longest, the shortest and one more sequence, three heads each, against the oracle."""
+    H, dh, N = 32, 128, 64
+    lens = list(I.workload("C4").prefix_len)
+    cases = [I.gen_attention_case(1004 + s, H, dh, L, N, "bf16") for s, L in enumerate(lens)]
+    batch = Batch([c[3] for c in cases], lens)
+    kp = np.full((H, batch.s_pool * dh), np.nan, np.float32)
+    vp = np.full((H, batch.s_pool * dh), np.nan, np.float32)
+    for s, (q, k, v, parent) in enumerate(cases):
+        layouts.kv_to_pool(k, v, batch.s_pool, int(batch.kv_off_h[s]), kp, vp)
+    dt = torch.bfloat16
+    out = torch.full((batch.T, H, dh), float("nan"), dtype=dt, device=DEV)
+    desc = b.ModelDesc(1, 64, H, dh, 64, 64, 1e-5, 1e4, b.BF16)
+    ws = torch.empty(b.trj_workspace_bytes(desc, batch.T, batch.B, batch.max_seq_slots),
+                     dtype=torch.uint8, device=DEV)
+    b.tree_attention(to_dev(np.concatenate([c[0] for c in cases]), dt), to_dev(kp, dt), to_dev(vp, dt),
+                     batch.parent, batch.node_off, batch.kv_off, batch.prefix, batch.B, batch.T, H, dh,
+                     batch.s_pool, batch.max_seq_slots, b.BF16, float(1 / np.sqrt(dh)), ws, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    heads = [0, 17, 31]
+    for s in (int(np.argmax(lens)), int(np.argmin(lens)), 7):
+        q, k, v, parent = cases[s]
+        want = O.tree_attention(q[:, heads], k[heads], v[heads], parent, lens[s])
+        assert rel_err(got[batch.rows(s)][:, heads], want) <= 1e-2, s
 
 
 def test_full_width_layer_against_oracle():
