@@ -324,7 +324,7 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
   if (B < 1 || T < 1 || T < B) return TRJ_ERR_BAD_SHAPE;
   if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
   return launch_tree_prep(parent, node_off, nullptr, nullptr, B, T, 0, 0, depth, anc, status_dev,
-                          nullptr, nullptr, nullptr, (hipStream_t)stream);
+                          nullptr, nullptr, nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
 int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
@@ -351,11 +351,10 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
   TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots, w.depth,
-                           w.anc,
-                           w.status, w.row_slot, w.row_pos, w.row_seq, st));
+                           w.anc, w.status, w.row_slot, w.row_pos, w.row_seq,
+                           // bf16: rows of malformed sequences read as zeros
+                           dtype == TRJ_BF16 ? out : nullptr, (size_t)T * n_heads * head_dim * 2, st));
   if (dtype == TRJ_BF16) {
-    // rows of malformed sequences read as zeros
-    TRJ_TRY(launch_zero_bytes(out, (size_t)T * n_heads * head_dim * 2, st));
     TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, w.status, B, w.attn_rows, w.attn_qg,
                               w.attn_bpwg, w.attn_ns, w.items, st));
     return launch_tree_attn_bf16((const uint16_t*)q, (const uint16_t*)k_layer,
@@ -464,8 +463,11 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
   float* lg = logits ? logits : w.logits;
   const float scale = 1.0f / sqrtf((float)dh);
 
+  // bf16: the attention output's padding rows and rows of malformed sequences stay zero all step
+  const bool bf16 = m.dtype == TRJ_BF16;
   TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots,
-                           w.t.depth, w.t.anc, status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq, st));
+                           w.t.depth, w.t.anc, status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq,
+                           bf16 ? w.op : nullptr, bf16 ? (size_t)padded_rows(T) * hd * 2 : 0, st));
   TRJ_TRY(launch_rope_table(w.t.row_pos, T, dh, m.rope_theta, w.cs, st));
   TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
 
@@ -474,8 +476,6 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
     TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg,
                               w.t.attn_bpwg, w.t.attn_ns, w.t.items, st));
-    // attention output: padding rows and rows of malformed sequences stay zero all step
-    TRJ_TRY(launch_zero_bytes(w.op, (size_t)tp * hd * 2, st));
     { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
                                w.hp, st)); }
     for (int l = 0; l < m.n_layers; ++l) {

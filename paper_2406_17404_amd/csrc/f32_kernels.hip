@@ -48,6 +48,22 @@ __global__ void embed_kernel(const E* __restrict__ embed, const int32_t* __restr
   int id = tok[t];
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
   const E* row = embed + (size_t)id * d;
+  if constexpr (sizeof(E) == 2) {
+    if ((d & 7) == 0) {  // 8 elements per load (rows are 16-byte aligned then)
+      const u32x4* r8 = reinterpret_cast<const u32x4*>(row);
+      f32x4* x8 = reinterpret_cast<f32x4*>(x + (size_t)t * d);
+      for (int g = threadIdx.x; g < (d >> 3); g += blockDim.x) {
+        const u32x4 v = r8[g];
+        f32x4 lo = {__builtin_bit_cast(float, v.x << 16), __builtin_bit_cast(float, v.x & 0xffff0000u),
+                    __builtin_bit_cast(float, v.y << 16), __builtin_bit_cast(float, v.y & 0xffff0000u)};
+        f32x4 hi = {__builtin_bit_cast(float, v.z << 16), __builtin_bit_cast(float, v.z & 0xffff0000u),
+                    __builtin_bit_cast(float, v.w << 16), __builtin_bit_cast(float, v.w & 0xffff0000u)};
+        x8[2 * g] = lo;
+        x8[2 * g + 1] = hi;
+      }
+      return;
+    }
+  }
   for (int c = threadIdx.x; c < d; c += blockDim.x) {
     if constexpr (sizeof(E) == 2) x[(size_t)t * d + c] = bf2f(row[c]);
     else x[(size_t)t * d + c] = row[c];
@@ -56,7 +72,7 @@ __global__ void embed_kernel(const E* __restrict__ embed, const int32_t* __restr
 int launch_embed(const void* embed, const int32_t* tok, int T, int d, int vocab, int dtype,
                  float* x, hipStream_t st) {
   if (dtype == TRJ_BF16)
-    embed_kernel<uint16_t><<<T, 256, 0, st>>>((const uint16_t*)embed, tok, d, vocab, x);
+    embed_kernel<uint16_t><<<T, 512, 0, st>>>((const uint16_t*)embed, tok, d, vocab, x);
   else
     embed_kernel<float><<<T, 256, 0, st>>>((const float*)embed, tok, d, vocab, x);
   return check_launch();

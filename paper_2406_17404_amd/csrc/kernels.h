@@ -37,7 +37,7 @@ struct ProfScope {
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                      const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
                      int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
-                     int32_t* row_seq, hipStream_t st);
+                     int32_t* row_seq, void* zero, size_t zero_bytes, hipStream_t st);
 // List of the (sequence, key split, query group) triples that exist, for the bf16 attention
 // launch: n records of 8 words {sequence, group, first row, rows, prefix length,
 // kv_off / 32, split, 1 if the sequence has more than one group}, sequences ordered by length (prefix + tree), longest first, when

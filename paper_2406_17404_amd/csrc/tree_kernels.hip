@@ -72,11 +72,15 @@ __global__ __launch_bounds__(TRJ_N_MAX) void tree_prep_kernel(
   }
 }
 
-// rows that no valid sequence covers must read as "skip": one launch clears all five arrays
+// rows that no valid sequence covers must read as "skip": one launch clears all five arrays,
+// and a further buffer of the caller's (the attention output, whose padding rows and rows of
+// malformed sequences must read as zeros)
 __global__ void prep_clear_kernel(int32_t* depth, int32_t* anc_words, int32_t* row_slot,
-                                  int32_t* row_pos, int32_t* row_seq, int T) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < 4 * T) anc_words[i] = 0;
+                                  int32_t* row_pos, int32_t* row_seq, int T, uint32_t* zero,
+                                  size_t zero_words) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < zero_words) zero[i] = 0;
+  if (i < (size_t)4 * T) anc_words[i] = 0;
   if (i < T) {
     depth[i] = 0;
     if (row_slot) {
@@ -164,9 +168,11 @@ int launch_attn_items(const int32_t* node_off, const int32_t* prefix_len, const 
 int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                      const int32_t* prefix_len, int B, int T, int s_pool, int max_seq_slots,
                      int32_t* depth, uint64_t* anc, int32_t* status_dev, int32_t* row_slot, int32_t* row_pos,
-                     int32_t* row_seq, hipStream_t st) {
-  prep_clear_kernel<<<(4 * T + 255) / 256, 256, 0, st>>>(depth, reinterpret_cast<int32_t*>(anc),
-                                                         row_slot, row_pos, row_seq, T);
+                     int32_t* row_seq, void* zero, size_t zero_bytes, hipStream_t st) {
+  const size_t zw = zero ? zero_bytes / 4 : 0, n = zw > (size_t)4 * T ? zw : (size_t)4 * T;
+  prep_clear_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+      depth, reinterpret_cast<int32_t*>(anc), row_slot, row_pos, row_seq, T,
+      static_cast<uint32_t*>(zero), zw);
   tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool,
                                             max_seq_slots, depth, anc, status_dev, row_slot, row_pos, row_seq);
   return check_launch();
@@ -174,7 +180,9 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
 
 // ------------------------------------------------------------------ greedy argmax
 // One workgroup per row; lowest index wins ties; NaN never compares greater.
-constexpr int ARGMAX_THREADS = 256;
+// One workgroup per row; every thread keeps ARGMAX_UNROLL 16-byte loads in flight (the row
+// is read once, so the kernel is a latency chain unless the loads are batched).
+constexpr int ARGMAX_THREADS = 1024, ARGMAX_UNROLL = 4;
 __device__ inline void amax_merge(float& bv, int& bi, float v, int i) {
   if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
 }
@@ -186,12 +194,21 @@ __global__ __launch_bounds__(ARGMAX_THREADS) void argmax_kernel(const float* __r
   const int tid = threadIdx.x;
   if ((V & 3) == 0 && (((uintptr_t)row) & 15) == 0) {
     const float4* r4 = reinterpret_cast<const float4*>(row);
-    for (int i = tid; i < (V >> 2); i += ARGMAX_THREADS) {
-      float4 x = r4[i];
-      amax_merge(bv, bi, x.x, 4 * i);
-      amax_merge(bv, bi, x.y, 4 * i + 1);
-      amax_merge(bv, bi, x.z, 4 * i + 2);
-      amax_merge(bv, bi, x.w, 4 * i + 3);
+    const int n4 = V >> 2;
+    for (int i0 = tid; i0 < n4; i0 += ARGMAX_THREADS * ARGMAX_UNROLL) {
+      float4 x[ARGMAX_UNROLL];
+#pragma unroll
+      for (int u = 0; u < ARGMAX_UNROLL; ++u) x[u] = r4[min(i0 + u * ARGMAX_THREADS, n4 - 1)];
+#pragma unroll
+      for (int u = 0; u < ARGMAX_UNROLL; ++u) {
+        const int i = i0 + u * ARGMAX_THREADS;
+        if (i < n4) {
+          amax_merge(bv, bi, x[u].x, 4 * i);
+          amax_merge(bv, bi, x[u].y, 4 * i + 1);
+          amax_merge(bv, bi, x[u].z, 4 * i + 2);
+          amax_merge(bv, bi, x[u].w, 4 * i + 3);
+        }
+      }
     }
   } else {
     for (int i = tid; i < V; i += ARGMAX_THREADS) amax_merge(bv, bi, row[i], i);
