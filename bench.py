@@ -338,7 +338,7 @@ def main():
     sweep, loop = None, None
     if B == 1 and not args.no_extras:
         sweep = []
-        for n in (1, 8, 16, 32, 64, 128):
+        for n in (1, 8, 16, 32, 64, 69, 96, 128):   # 69 = the 63-node template + a retrieval path of 5 + the root
             par_n, tok_n = i32(np.arange(-1, n - 1)), i32(tok_h[:1].repeat(n))
             off_n = i32([0, n])
             ws_n = torch.empty(b.trj_workspace_bytes(desc, n, 1, L + n), dtype=torch.uint8, device=dev)

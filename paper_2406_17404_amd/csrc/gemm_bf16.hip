@@ -269,7 +269,7 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
 template <int MT, int RT, int KW, class Epi>
 static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
                      int split_k, const Epi& epi, hipStream_t st) {
-  constexpr int PH = MT == 4 ? 16 : 32;
+  constexpr int PH = MT >= 3 ? 16 : 32;
   constexpr int WS = PH / KW;
   constexpr int PF = WS < 16 ? WS : 16;
   int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
@@ -442,7 +442,7 @@ struct GemmPlan {
 };
 static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   GemmPlan g;
-  g.mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
+  g.mt = tp <= 96 ? tp / 32 : 4;
   const int ntiles = n_out >> 5, tblocks = tp / (32 * g.mt);
   if (split_k < 1) split_k = 1;
   auto splits = [&](int ph) {  // grid splits a request really gets: never an empty one
@@ -468,13 +468,13 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   const int rgt = 4 * g.wt;  // row tiles per workgroup of the many-rows kernel
   g.big = g.mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t &&
           (long)((ntiles + rgt - 1) / rgt) * tblocks * splits(BIG_PH) >= 128;
-  g.ph = g.big ? BIG_PH : (g.mt == 4 ? 16 : 32);
+  g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);
   g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
-  if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt == 4 ? 3 : 2);
+  if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt >= 3 ? 3 : 2);
   // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
   // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
-  if (shape == 1 && g.mt == 4 && g_tune.gemm_cfg == 0) shape = 4;
+  if (shape == 1 && g.mt >= 3 && g_tune.gemm_cfg == 0) shape = 4;
   // 128 token rows, long k-range per workgroup: four k-parts (8 wavefronts) keep twice the
   // loads in flight per compute unit (QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us; the output
   // projection's 64 k-steps per split are too short for it, 17.3 against 18.0 us)
@@ -505,7 +505,7 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
   } while (0)
   if (g.big && g.wt == 4) launch_t<4, 4, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
   else if (g.big) launch_t<4, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);
-  else if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else TRJ_P(4);
+  else if (g.mt == 1) TRJ_P(1); else if (g.mt == 2) TRJ_P(2); else if (g.mt == 3) TRJ_P(3); else TRJ_P(4);
 #undef TRJ_P
   return check_launch();
 }
@@ -518,7 +518,7 @@ int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k) {
 int gemm_bf16_split_k(int n_out, int tp, int n_in) {
   // projections whose epilogue is a plain partial-sum store are split along k until the
   // launch has about one workgroup (of 2 row tiles) per compute unit
-  int mt = tp == 32 ? 1 : (tp == 64 ? 2 : 4);
+  int mt = tp <= 96 ? tp / 32 : 4;
   int groups = ((n_out / 32 + 1) / 2) * (tp / (32 * mt));
   if (mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t)
     groups = ((n_out / 32 + 7) / 8) * (tp / 128);  // 8 row tiles per workgroup there

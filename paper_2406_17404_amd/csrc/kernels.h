@@ -120,6 +120,8 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
 size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_slots);
 int check_model(const trj_model_desc* m);
 
-inline int padded_rows(int T) { return T <= 32 ? 32 : (T <= 64 ? 64 : (T + 127) / 128 * 128); }
+// token rows are padded to whole 32-row MFMA tiles: 1, 2, 3 or 4 tiles per workgroup pass,
+// beyond that blocks of 4
+inline int padded_rows(int T) { return T <= 96 ? (T <= 32 ? 32 : (T + 31) / 32 * 32) : (T + 127) / 128 * 128; }
 
 }  // namespace trj

@@ -45,7 +45,7 @@ def dev_normal(shape, std, seed):
                                              # the grouped-query 8B shape's projections
                                              ("qkv_gqa", 4096, 6144), ("gate_up_8b", 4096, 28672),
                                              ("down_8b", 14336, 4096)])
-@pytest.mark.parametrize("T", [64, 128, 1024])
+@pytest.mark.parametrize("T", [64, 69, 128, 1024])
 def test_projection_shapes_sampled(name, n_in, n_out, T):
     w = dev_normal((n_out, n_in), 0.02, 11)
     x = dev_normal((T, n_in), 1.0, 12)

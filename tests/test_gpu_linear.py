@@ -30,6 +30,8 @@ def run_linear(dtype, T, n_in, n_out, split_k, seed=0):
 @pytest.mark.parametrize("T,n_in,n_out,split_k", [
     (1, 16, 32, 0), (15, 256, 96, 0), (64, 4096, 512, 1), (64, 4096, 512, 4), (33, 1040, 160, 3),
     (128, 688, 96, 0), (100, 2048, 256, 2), (200, 512, 64, 0), (64, 11008, 128, 8),
+    # 65..96 rows: three row tiles per pass (every workgroup shape the plan picks there)
+    (69, 4096, 512, 0), (96, 1040, 160, 3), (80, 2064, 4128, 1), (65, 11008, 256, 4), (90, 4096, 6144, 1),
     # many rows: the kernel whose wavefronts own two row tiles (ragged row-tile count, split-k,
     # a k-range that ends inside a phase, rows that are not a multiple of 128)
     (256, 1024, 4096, 0), (512, 2064, 4128, 0), (1000, 512, 8192, 3), (1024, 4096, 2080, 2),
@@ -44,7 +46,7 @@ def test_bf16_linear(T, n_in, n_out, split_k):
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("T,n_in,n_out,split_k", [(64, 1040, 160, 1), (33, 4096, 6144, 1), (128, 2064, 96, 3),
-                                                  (20, 528, 416, 2)])
+                                                  (20, 528, 416, 2), (69, 1040, 224, 2)])
 def test_bf16_linear_every_workgroup_shape(cfg, T, n_in, n_out, split_k):
     """Row tiles x k-parts per workgroup forced to each of the five shapes (row-tile counts
     that do not divide by the shape's rows, a k-range that ends inside a phase)."""

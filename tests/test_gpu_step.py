@@ -111,7 +111,7 @@ def test_tiny_workload_fp32_planted_acceptance():
     assert summary[0][2] == 0
 
 
-@pytest.mark.parametrize("n_tree,L", [(15, 128), (64, 300), (128, 77), (1, 40), (33, 0)])
+@pytest.mark.parametrize("n_tree,L", [(15, 128), (64, 300), (128, 77), (1, 40), (33, 0), (69, 200), (96, 31)])
 def test_small_bf16_model(n_tree, L):
     """A shrunken bf16 decoder (4 layers, d 512, 4x128 heads, FFN 1408, vocab 1024) with
     the 7B workload's recipe: N(0, 0.02) weights, N(0,1) prefix K/V, c1-style tree."""
