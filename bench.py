@@ -439,6 +439,12 @@ def main():
         "roofline": roof, "kernels": kernels, "event_pair_us": event_pair_us and round(event_pair_us, 2),
         "cpu_baseline": cpu,
         "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,
+        # context only (another machine, trained weights, end-to-end decoding): the paper's
+        # Table 1, TR-Jacobi decoding with MSN-trained models against autoregressive decoding
+        "paper_context": {"hardware": "one NVIDIA A100-80G, batch 1",
+                          "LLaMA3-8B MSN + TR-Jacobi": "99.32 tokens/s, 2.28x over autoregressive",
+                          "DeepseekCoder-6.7B MSN + TR-Jacobi": "128.50 tokens/s, 2.68x over autoregressive",
+                          "note": "not comparable with `value` (a step rate on random-init weights); not the target"},
         "planted_acceptance": planted,
     }
     print(json.dumps(out))
