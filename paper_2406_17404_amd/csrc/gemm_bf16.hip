@@ -266,10 +266,17 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
   }
 }
 
+// k-steps per LDS phase of gemm_p_kernel.  Every wavefront walks 8 k-steps per phase with
+// 2 or 4 k-parts; with one k-part the phase itself is 8 k-steps: the activations then
+// arrive in bursts of 16 KiB per workgroup instead of 64, which disturbs the weight
+// stream less (gate/up 37.9 -> 35.5 us, LM head 49.4 -> 46.8 us; 16 k-steps: 37.3 us,
+// 4 k-steps, a ring of only 4: 44.6 us).
+constexpr int p_phase(int mt, int kw) { return kw == 1 ? 8 : (mt >= 3 ? 16 : 32); }
+
 template <int MT, int RT, int KW, class Epi>
 static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
                      int split_k, const Epi& epi, hipStream_t st) {
-  constexpr int PH = MT >= 3 ? 16 : 32;
+  constexpr int PH = p_phase(MT, KW);
   constexpr int WS = PH / KW;
   constexpr int PF = WS < 16 ? WS : 16;
   int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
@@ -468,7 +475,7 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   const int rgt = 4 * g.wt;  // row tiles per workgroup of the many-rows kernel
   g.big = g.mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t &&
           (long)((ntiles + rgt - 1) / rgt) * tblocks * splits(BIG_PH) >= 128;
-  g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);
+  g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);  // provisional: the shape decides it below
   g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt >= 3 ? 3 : 2);
@@ -486,6 +493,10 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   g.rt = (shape == 1 || shape == 4) ? 4 : (shape == 5 ? 1 : 2);
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : (shape == 5 ? 8 : 2));
   if (g.big) { g.rt = 4; g.kw = 1; }
+  else {
+    g.ph = p_phase(g.mt, g.kw);
+    g.split_k = splits(g.ph);  // what launch_p computes from the same request
+  }
   return g;
 }
 
