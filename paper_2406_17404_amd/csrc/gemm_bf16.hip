@@ -23,6 +23,8 @@
 // it is LDS bandwidth and where the re-used weight rows come from.  gemm_t_kernel below
 // keeps the structure but gives every wavefront two row tiles and places the workgroups
 // that share weight rows on one die.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -147,7 +149,10 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
   constexpr int WS = PH / KW;             // k-steps per wavefront and phase
   constexpr int XG = PH * MT * 64;        // 16-byte granules per phase buffer
   constexpr int XL = XG / (NWV * 64);     // activation loads per lane and phase
-  static_assert(PH % KW == 0 && WS % PF == 0 && XG % (NWV * 64) == 0, "phase shape");
+  // the weight ring holds PF k-steps: a divisor of a phase's WS steps, or RP whole phases
+  constexpr int RP = PF > WS ? PF / WS : 1;
+  static_assert(PH % KW == 0 && (WS % PF == 0 || PF % WS == 0) && RP <= 4 &&
+                    XG % (NWV * 64) == 0, "phase shape");
   extern __shared__ __align__(16) uint8_t smem[];
   u32x4* lds = reinterpret_cast<u32x4*>(smem);
 
@@ -213,27 +218,35 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
     x_load(ph0 + 1);
     lds_barrier();
     int i = 0;
-    for (int ph = ph0; ph < ph1; ++ph) {
+    // one phase; PAR = its place in the ring's trip when the ring spans several phases
+    auto phase = [&](int ph, auto par_c) {
+      constexpr int PAR = decltype(par_c)::value;
       const int buf = (ph - ph0) & 1;
 #pragma unroll
-      for (int r = 0; r < WS / PF; ++r) {
+      for (int q = 0; q < WS; ++q) {
+        const int slot = (PAR * WS + q) % PF;  // compile-time after unrolling
+        bf16x8 wa = __builtin_bit_cast(bf16x8, wr[slot]);
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-          bf16x8 wa = __builtin_bit_cast(bf16x8, wr[p]);
-#pragma unroll
-          for (int m = 0; m < MT; ++m) {
-            bf16x8 xb = __builtin_bit_cast(
-                bf16x8, lds[buf * XG + ((kw * WS + r * PF + p) * MT + m) * 64 + lane]);
-            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[m], 0, 0, 0);
-          }
-          wr[p] = w_load(i + r * PF + p + PF);
-          __builtin_amdgcn_sched_barrier(0);  // keep each reload next to its step
+        for (int m = 0; m < MT; ++m) {
+          bf16x8 xb = __builtin_bit_cast(
+              bf16x8, lds[buf * XG + ((kw * WS + q) * MT + m) * 64 + lane]);
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xb, acc[m], 0, 0, 0);
         }
+        wr[slot] = w_load(i + q + PF);
+        __builtin_amdgcn_sched_barrier(0);  // keep each reload next to its step
       }
       i += WS;
       x_store(buf ^ 1, ph + 1);  // activations of the next phase (unused after the last one)
       lds_barrier();
       x_load(ph + 2);
+    };
+    for (int ph = ph0; ph < ph1; ph += RP) {
+      phase(ph, std::integral_constant<int, 0>{});
+      if constexpr (RP >= 2) { if (ph + 1 < ph1) phase(ph + 1, std::integral_constant<int, 1>{}); }
+      if constexpr (RP >= 4) {
+        if (ph + 2 < ph1) phase(ph + 2, std::integral_constant<int, 2>{});
+        if (ph + 3 < ph1) phase(ph + 3, std::integral_constant<int, 3>{});
+      }
     }
   }
 
@@ -266,19 +279,20 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
   }
 }
 
-// k-steps per LDS phase of gemm_p_kernel.  Every wavefront walks 8 k-steps per phase with
-// 2 or 4 k-parts; with one k-part the phase itself is 8 k-steps: the activations then
-// arrive in bursts of 16 KiB per workgroup instead of 64, which disturbs the weight
-// stream less (gate/up 37.9 -> 35.5 us, LM head 49.4 -> 46.8 us; 16 k-steps: 37.3 us,
-// 4 k-steps, a ring of only 4: 44.6 us).
-constexpr int p_phase(int mt, int kw) { return kw == 1 ? 8 : (mt >= 3 ? 16 : 32); }
+// k-steps per LDS phase of gemm_p_kernel: 8 with one k-part, 16 otherwise.  Short phases
+// bring the activations in bursts of 16-32 KiB per workgroup instead of 64, which disturbs
+// the weight stream less (one k-part: gate/up 37.9 -> 35.5 us, LM head 49.4 -> 46.8 us with
+// 8 k-steps, 37.3 us with 16, 44.6 us with 4 and a ring of only 4; four k-parts: down
+// 23.5 -> 21.8 us with 16 k-steps, worse again with 8).  The weight ring stays 8 k-steps
+// deep and then spans two or four phases (16 deep: 36.6 us for gate/up).
+constexpr int p_phase(int mt, int kw) { return kw == 1 ? 8 : 16; }
 
 template <int MT, int RT, int KW, class Epi>
 static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
                      int split_k, const Epi& epi, hipStream_t st) {
   constexpr int PH = p_phase(MT, KW);
   constexpr int WS = PH / KW;
-  constexpr int PF = WS < 16 ? WS : 16;
+  constexpr int PF = WS < 8 ? 8 : (WS < 16 ? WS : 16);
   int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
   if (split_k < 1) split_k = 1;
   if (split_k > nph) split_k = nph;
