@@ -492,13 +492,14 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);  // provisional: the shape decides it below
   g.split_k = splits(g.ph);
   int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
-  if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : (g.mt >= 3 ? 3 : 2);
+  if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : 3;
   // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
   // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
   if (shape == 1 && g.mt >= 3 && g_tune.gemm_cfg == 0) shape = 4;
-  // 128 token rows, long k-range per workgroup: four k-parts (8 wavefronts) keep twice the
-  // loads in flight per compute unit (QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us; the output
-  // projection's 64 k-steps per split are too short for it, 17.3 against 18.0 us)
+  // long k-range per workgroup: four k-parts (8 wavefronts) keep twice the loads in flight
+  // per compute unit (128 rows: QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us); the output
+  // projection's 64 k-steps per split are too short for it (128 rows: 17.3 against 18.0 us;
+  // 64 rows: 12.9 against 13.7 us)
   if (shape == 3 && g_tune.gemm_cfg == 0 && (n_in >> 4) / g.split_k >= 128) shape = 2;
   // few row tiles (the QKV projection of a grouped-query model: 192): one row tile per
   // workgroup and eight k-parts, so that the launch still has a workgroup on most compute
