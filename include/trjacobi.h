@@ -15,8 +15,10 @@
  *  - C linkage, plain pointers and sizes.  Every function returns a trj_status.
  *    Nothing throws, nothing aborts.
  *  - Pointers are DEVICE pointers unless the name starts with h_ (host).  The caller
- *    owns every buffer; the library allocates and frees nothing and keeps no state
- *    besides the last HIP error code.
+ *    owns every buffer; the library allocates and frees nothing.  Process-wide state: the
+ *    last HIP error code, and what the development header trjacobi_dev.h adds (launch
+ *    knobs, an event timer).  Entry points may be called from several threads as long as
+ *    their buffers do not overlap.
  *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL
  *    is the default stream) and returns; no host synchronisation happens inside.
  *  - Errors the host can see (null pointers, shapes, dtype, sizes) are returned
@@ -133,49 +135,6 @@ int32_t trj_kv_unpack(void* k_plain, void* v_plain, const void* k_pool, const vo
                       int32_t n_heads, int32_t head_dim, int32_t s_pool, int32_t slot0,
                       int32_t n_slots, int32_t dtype, void* stream);
 
-/* One projection alone (tests, roofline measurements): y[T][n_out] (fp32) = x W^T with
- * x[T][n_in] plain row-major in `dtype` and W a TRJ_PACK_PLAIN matrix.  split_k <= 0
- * lets the library choose.  workspace: at least
- * 2*ceil(T/128)*128*n_in + 4*8*T*n_out + 1024 bytes. */
-int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in, int32_t n_out,
-                   int32_t dtype, int32_t split_k, void* workspace, size_t ws_bytes, float* y,
-                   void* stream);
-
-/* Launch-shape knobs for experiments: "gemm_target_wgs" (workgroups a split-k projection
- * is split up to), "max_split_k", "gemm_cfg" (0: choose the workgroup shape per
- * projection, 1..5 force one), "gemm_big_t" (padded token rows from which the packed-batch
- * projection kernel is used, 0: never), "gemm_big_wt" (row tiles per wavefront of that
- * kernel: 2, 4, or 0 to choose per projection), "attn_target_wgs" (attention workgroups aimed at
- * per launch), "attn_min_bpw" (32-slot blocks per wavefront, at least), "attn_xchg_min_blocks" (blocks
- * per workgroup from which the two wavefronts of a key stream split their K/V loads and
- * exchange halves through LDS).  Results do not
- * depend on them beyond fp32 summation order.  Unknown name: TRJ_ERR_BAD_SHAPE. */
-int32_t trj_set_tunable(const char* name, int32_t value);
-
-/* Per-kernel timing for benchmarks.  Between trj_profile_begin(kernel_class, capacity)
- * and trj_profile_end, every launch of that kernel class inside the entry points is
- * bracketed by HIP events on its stream (the only HIP objects this library ever
- * creates).  trj_profile_end waits for them, writes up to `capacity` durations in
- * milliseconds to h_ms, their number to h_count, and destroys the events.  Classes:
- * 1 QKV projection, 2 tree attention, 3 attention merge, 4 output projection, 5 split-k
- * sum + residual + RMSNorm, 6 gate/up projection, 7 down projection, 8 LM head, 9 argmax,
- * 10 accept, 11 KV compaction. */
-int32_t trj_profile_begin(int32_t kernel_class, int32_t capacity);
-/* The same with a span: the start event goes before a launch of `first_class`, the stop
- * event after the next launch of `last_class` (which the entry point issues later in the
- * same step).  The difference between a span [A..B] and the single class B is the
- * duration of A up to the start of B without the cost of the event pair itself. */
-int32_t trj_profile_begin_span(int32_t first_class, int32_t last_class, int32_t capacity);
-int32_t trj_profile_end(float* h_ms, int32_t capacity, int32_t* h_count);
-/* Average elapsed time between two events recorded back to back on `stream` (nothing
- * between them): the part of a trj_profile_* duration that is the event pair itself, not
- * the kernel it brackets.  `pairs` in 1..4096; synchronises the stream. */
-int32_t trj_profile_event_overhead(int32_t pairs, float* h_avg_ms, void* stream);
-
-/* Measurement aid: a plain copy of `bytes` (a multiple of 16) from src to dst, used to
- * calibrate the HBM traffic counters against a kernel whose traffic is known. */
-int32_t trj_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
-
 /* Tree bookkeeping: depth[i] = depth[parent[i]] + 1 (root 0) and the ancestor-or-self
  * bit rows of the sparse tree mask (appendix "Templates for Token Tree"): bit j%64 of
  * anc[i][j/64] is set when node j is on the path root..i.  A sequence whose tree is
@@ -200,6 +159,11 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
                        int32_t n_kv_heads, int32_t head_dim, int32_t s_pool,
                        int32_t max_seq_slots, int32_t dtype, float scale, void* workspace,
                        size_t ws_bytes, void* out, void* stream);
+
+/* Bytes of device scratch tree_attention alone needs at these sizes (at most what
+ * trj_workspace_bytes reports for a model with these heads). */
+int32_t tree_attention_workspace_bytes(int32_t B, int32_t T, int32_t n_heads, int32_t head_dim,
+                                       int32_t max_seq_slots, int32_t dtype, size_t* h_bytes);
 
 /* Greedy argmax (Eq. 1) and the longest accepted path (section "TR-Jacobi Decoding").
  * If logits != NULL: argmax_out[i] = lowest index of the row maximum of logits[i][0..V)

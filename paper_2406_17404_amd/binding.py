@@ -1,4 +1,5 @@
-"""ctypes binding of libtrjacobi.so: the same names and arguments as include/trjacobi.h.
+"""ctypes binding of libtrjacobi.so: the same names and arguments as include/trjacobi.h
+and include/trjacobi_dev.h.
 
 Only argument marshalling happens here: torch tensors stand for device buffers (their
 ``data_ptr()`` is passed), the current torch stream is passed as the HIP stream, and a
@@ -66,6 +67,7 @@ _SIGS = {
     "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
     "trj_profile_event_overhead": (_i32, [_i32, C.POINTER(C.c_float), _vp]),
     "trj_copy_probe": (_i32, [_vp, _vp, _sz, _vp]),
+    "trj_dev_gemm_plan": (_i32, [_i32, _i32, _i32, _i32, _ip]),
     "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
     "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "trj_kv_pack": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -73,6 +75,7 @@ _SIGS = {
     "trj_linear": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp, _vp]),
     "trj_tree_mask": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
     "tree_attention": (_i32, [_vp] * 7 + [_i32] * 8 + [_f, _vp, _sz, _vp, _vp]),
+    "tree_attention_workspace_bytes": (_i32, [_i32] * 6 + [C.POINTER(_sz)]),
     "accept_path": (_i32, [_vp] * 4 + [_i32] * 3 + [_vp] * 7),
     "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
     "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
@@ -174,6 +177,13 @@ def trj_copy_probe(dst, src, nbytes: int) -> None:
     _check("trj_copy_probe", lib().trj_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream()))
 
 
+def trj_dev_gemm_plan(T: int, n_in: int, n_out: int, fused: bool) -> dict:
+    out = (C.c_int32 * 6)()
+    _check("trj_dev_gemm_plan", lib().trj_dev_gemm_plan(T, n_in, n_out, int(fused), out))
+    return dict(zip(("token_tiles", "row_tiles", "k_parts", "tiles_per_wave", "split_k", "many_rows"),
+                    (int(v) for v in out)))
+
+
 def trj_workspace_bytes(desc: ModelDesc, t_max: int, b_max: int, l_max: int) -> int:
     n = _sz(0)
     _check("trj_workspace_bytes", lib().trj_workspace_bytes(C.byref(desc), t_max, b_max, l_max, C.byref(n)))
@@ -212,6 +222,13 @@ def tree_attention(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B,
         _ptr(q), _ptr(k_layer), _ptr(v_layer), _ptr(parent), _ptr(node_off), _ptr(kv_off),
         _ptr(prefix_len), B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), _stream()))
+
+
+def tree_attention_workspace_bytes(B, T, n_heads, head_dim, max_seq_slots, dtype) -> int:
+    n = _sz(0)
+    _check("tree_attention_workspace_bytes", lib().tree_attention_workspace_bytes(
+        B, T, n_heads, head_dim, max_seq_slots, dtype, C.byref(n)))
+    return int(n.value)
 
 
 def accept_path(logits, tok, parent, node_off, B, T, V, argmax_out, accept_len, best_node, path,

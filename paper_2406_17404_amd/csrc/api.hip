@@ -2,14 +2,29 @@
 // in which the kernels of the verify step are enqueued.  No arithmetic lives here.
 #include <atomic>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
+#include "../../include/trjacobi_dev.h"
 #include "common.h"
 #include "kernels.h"
 
 namespace trj {
 
-Tunables g_tune;
+static Tunables g_tune;          // process-wide, written by trj_set_tunable under g_tune_mu
+static std::mutex g_tune_mu;
+static thread_local const Tunables* t_tune = nullptr;  // the running entry point's snapshot
+const Tunables& tune() { return t_tune ? *t_tune : g_tune; }
+TuneScope::TuneScope() : prev(t_tune) {
+  if (prev) {
+    snap = *prev;  // nested entry point: keep the outer call's values
+  } else {
+    std::lock_guard<std::mutex> lk(g_tune_mu);
+    snap = g_tune;
+  }
+  t_tune = &snap;
+}
+TuneScope::~TuneScope() { t_tune = prev; }
 static std::atomic<int> g_last_hip_error{0};
 void note_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 
@@ -117,10 +132,12 @@ static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max
 static int check_desc(const trj_model_desc* m) {
   if (!m) return TRJ_ERR_NULLPTR;
   if (m->dtype != TRJ_F32 && m->dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
-  if (m->n_layers < 1 || m->d_model < 16 || m->n_heads < 1 || m->head_dim < 32 || m->d_ffn < 16 ||
+  if (m->n_layers < 1 || m->d_model < 32 || m->n_heads < 1 || m->head_dim < 32 || m->d_ffn < 32 ||
       m->vocab < 32)
     return TRJ_ERR_BAD_SHAPE;
-  if ((m->d_model & 15) || (m->head_dim & 31) || (m->d_ffn & 15) || (m->vocab & 31))
+  // every projection's output width is a whole number of 32-row weight tiles (d_model for
+  // the output and down projections, 2 * d_ffn in gate/up pairs of 16 + 16 rows)
+  if ((m->d_model & 31) || (m->head_dim & 31) || (m->d_ffn & 31) || (m->vocab & 31))
     return TRJ_ERR_BAD_SHAPE;
   if (m->dtype == TRJ_BF16 && m->head_dim != 64 && m->head_dim != 128) return TRJ_ERR_BAD_SHAPE;
   if (m->dtype == TRJ_BF16 && m->d_model > 8192) return TRJ_ERR_BAD_SHAPE;
@@ -158,6 +175,7 @@ int32_t trj_last_hip_error(void) { return g_last_hip_error.load(); }
 // refused (a zero here would otherwise divide by zero in the plan).
 int32_t trj_set_tunable(const char* name, int32_t value) {
   if (!name) return TRJ_ERR_NULLPTR;
+  std::lock_guard<std::mutex> lk(g_tune_mu);
   const bool positive = value >= 1 && value <= (1 << 20);
   if (!strcmp(name, "gemm_target_wgs") && positive) g_tune.gemm_target_wgs = value;
   else if (!strcmp(name, "max_split_k") && positive) g_tune.max_split_k = value;
@@ -253,6 +271,7 @@ int32_t trj_workspace_bytes(const trj_model_desc* desc, int32_t t_max, int32_t b
   if (!h_bytes) return TRJ_ERR_NULLPTR;
   TRJ_TRY(check_desc(desc));
   if (t_max < 1 || b_max < 1 || l_max < 1) return TRJ_ERR_BAD_SHAPE;
+  TuneScope tune_scope;
   Carver c(nullptr);
   StepWs w;
   carve_step(c, *desc, b_max, t_max, l_max, true, &w);
@@ -327,14 +346,14 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
                           nullptr, nullptr, nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
-int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
+static int tree_attention_impl(const void* q, const void* k_layer, const void* v_layer,
                        const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                        const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
                        int32_t n_kv_heads, int32_t head_dim, int32_t s_pool, int32_t max_seq_slots,
-                       int32_t dtype, float scale, void* workspace, size_t ws_bytes, void* out,
-                       void* stream) {
-  if (!q || !k_layer || !v_layer || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
-      !out)
+                       int32_t dtype, float scale, bool static_ws, void* workspace, size_t ws_bytes,
+                       void* out, void* stream) {
+  if (!q || !k_layer || !v_layer || !parent || !node_off || !kv_off || !prefix_len || !out ||
+      (!static_ws && !workspace))
     return TRJ_ERR_NULLPTR;
   if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
   TRJ_TRY(check_batch(B, T, s_pool, max_seq_slots));
@@ -345,6 +364,8 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   if (dtype == TRJ_F32 && (size_t)(head_dim + max_seq_slots) * 4 > 64 * 1024)
     return TRJ_ERR_BAD_SHAPE;
   if (!(scale > 0.f)) return TRJ_ERR_BAD_SHAPE;
+  TuneScope tune_scope;
+  if (static_ws) return TRJ_ERR_BAD_SHAPE;
   Carver c(workspace);
   TreeWs w;
   carve_tree(c, dtype, B, T, n_heads, head_dim, max_seq_slots, &w);
@@ -365,6 +386,32 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   return launch_tree_attn_f32((const float*)q, (const float*)k_layer, (const float*)v_layer, w.anc,
                               w.row_seq, node_off, kv_off, prefix_len, w.status, T, n_heads,
                               n_kv_heads, head_dim, s_pool, max_seq_slots, scale, (float*)out, st);
+}
+
+int32_t tree_attention_workspace_bytes(int32_t B, int32_t T, int32_t n_heads, int32_t head_dim,
+                                       int32_t max_seq_slots, int32_t dtype, size_t* h_bytes) {
+  if (!h_bytes) return TRJ_ERR_NULLPTR;
+  if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
+  if (B < 1 || T < B || max_seq_slots < 1 || n_heads < 1 || head_dim < 32 || (head_dim & 31))
+    return TRJ_ERR_BAD_SHAPE;
+  if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  TuneScope tune_scope;
+  Carver c(nullptr);
+  TreeWs w;
+  carve_tree(c, dtype, B, T, n_heads, head_dim, max_seq_slots, &w);
+  *h_bytes = align_up(c.off, 256);
+  return TRJ_OK;
+}
+
+int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
+                       const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
+                       const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
+                       int32_t n_kv_heads, int32_t head_dim, int32_t s_pool, int32_t max_seq_slots,
+                       int32_t dtype, float scale, void* workspace, size_t ws_bytes, void* out,
+                       void* stream) {
+  return tree_attention_impl(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T, n_heads,
+                             n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale, false,
+                             workspace, ws_bytes, out, stream);
 }
 
 int32_t accept_path(const float* logits, const int32_t* tok, const int32_t* parent,
@@ -408,6 +455,7 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   if (dtype != TRJ_F32 && dtype != TRJ_BF16) return TRJ_ERR_BAD_DTYPE;
   if (T < 1 || n_in < 16 || n_out < 32 || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
   hipStream_t st = (hipStream_t)stream;
+  TuneScope tune_scope;
   if (dtype == TRJ_F32)
     return launch_gemm_f32((const float*)x, (const float*)w_packed, T, n_in, n_out, 0, y, st);
   const int tp = padded_rows(T);
@@ -420,6 +468,18 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   if (sk == 1) return launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, 1, y, st);
   TRJ_TRY(launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, sk, part, st));
   return launch_sum_splits(part, sk, (size_t)T * n_out, y, st);
+}
+
+// Which kernel shape a bf16 projection of the step gets: fused != 0 for the QKV and gate/up
+// projections (their epilogues rule out a k-split across workgroups), else the split the
+// step itself would ask for.
+int32_t trj_dev_gemm_plan(int32_t T, int32_t n_in, int32_t n_out, int32_t fused, int32_t* h_plan) {
+  if (!h_plan) return TRJ_ERR_NULLPTR;
+  if (T < 1 || n_in < 16 || n_out < 32 || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
+  TuneScope tune_scope;
+  const int tp = padded_rows(T);
+  gemm_bf16_describe_plan(tp, n_in, n_out, fused ? 1 : gemm_bf16_split_k(n_out, tp, n_in), h_plan);
+  return TRJ_OK;
 }
 
 }  // extern "C"
@@ -456,6 +516,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
     return TRJ_ERR_BAD_SHAPE;
   if (m.dtype == TRJ_F32 && (size_t)(dh + max_seq_slots) * 4 > 64 * 1024) return TRJ_ERR_BAD_SHAPE;
 
+  TuneScope tune_scope;
   Carver c(workspace);
   StepWs w;
   carve_step(c, m, B, T, max_seq_slots, with_head && logits == nullptr, &w);
@@ -527,6 +588,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
 
 // workspace bytes of one step_impl call (pure arithmetic)
 size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_slots) {
+  TuneScope tune_scope;
   Carver c(nullptr);
   StepWs w;
   carve_step(c, m, B, T, max_seq_slots, true, &w);

@@ -483,8 +483,8 @@ void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int*
   const int rows = 32 * *ntw;
   const int items_est = B > (T + rows - 1) / rows ? B : (T + rows - 1) / rows;
   long cols = (long)items_est * n_heads;
-  int b = (int)((nb * cols + g_tune.attn_target_wgs - 1) / g_tune.attn_target_wgs);
-  if (b < g_tune.attn_min_bpw * ks) b = g_tune.attn_min_bpw * ks;
+  int b = (int)((nb * cols + tune().attn_target_wgs - 1) / tune().attn_target_wgs);
+  if (b < tune().attn_min_bpw * ks) b = tune().attn_min_bpw * ks;
   if (b > nb) b = nb;
   *bpwg = b;
   *nsplit_max = (nb + b - 1) / b;
@@ -525,7 +525,7 @@ int launch_tree_attn_bf16(const uint16_t* q, const uint16_t* k_layer, const uint
   // reads: one query head per K/V head, and trees of at most 64 nodes (known here only on
   // average; a sequence with more runs the exchange without the hint, 3-6 % slower than
   // the plain pair).
-  const bool xchg = ntw == 2 && bpwg >= g_tune.attn_xchg_min_blocks && n_heads == n_kv_heads &&
+  const bool xchg = ntw == 2 && bpwg >= tune().attn_xchg_min_blocks && n_heads == n_kv_heads &&
                     T <= 64 * B;
   if (xchg) {  // 2 buffers x streams x halves x pieces
     size_t xch = (size_t)2 * ks * 2 * (dh / 32 + dh / 32) * 1024;

@@ -230,6 +230,7 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
   if (s_pool < prompt_len + max_new + N || (s_pool & (TRJ_KV_BLOCK - 1))) return TRJ_ERR_BAD_SHAPE;
   for (int i = 0; i < prompt_len; ++i)
     if (h_prompt[i] < 0 || h_prompt[i] >= desc->vocab) return TRJ_ERR_BAD_SHAPE;
+  TuneScope tune_scope;  // one set of launch-shape knobs for the whole generation
   size_t need;
   TRJ_TRY(tr_jacobi_generate_workspace_bytes(desc, N, prompt_len, max_new, s_pool, &need));
   if (ws_bytes < need) return TRJ_ERR_WORKSPACE_TOO_SMALL;

@@ -130,6 +130,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 }
 int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, int add_to,
                     float* y, hipStream_t st) {
+  if (T < 1 || n_in < 16 || n_out < 32 || (n_in & 15) || (n_out & 31)) return TRJ_ERR_BAD_SHAPE;
   dim3 grid(n_out / 32, (T + 7) / 8);
   gemm_f32_kernel<<<grid, 256, 0, st>>>(x, w, T, n_in, n_out, add_to, y);
   return check_launch();

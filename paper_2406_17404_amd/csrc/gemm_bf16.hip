@@ -480,31 +480,31 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   // faster by 5-10 % for 12288, 16384, 28672, 32000, 65536 output rows, slower by 10 % for
   // 22016, where the last round is a third full); split-k launches stay with two.
   g.wt = 2;
-  if (g_tune.gemm_big_wt == 4) g.wt = 4;
-  else if (g_tune.gemm_big_wt == 0 && split_k == 1) {
+  if (tune().gemm_big_wt == 4) g.wt = 4;
+  else if (tune().gemm_big_wt == 0 && split_k == 1) {
     const long wgs4 = (long)((ntiles + 15) / 16) * tblocks;
     const long last = wgs4 % 256;
     if (wgs4 >= 128 && (last == 0 || last >= 154)) g.wt = 4;
   }
   const int rgt = 4 * g.wt;  // row tiles per workgroup of the many-rows kernel
-  g.big = g.mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t &&
+  g.big = g.mt == 4 && tune().gemm_big_t > 0 && tp >= tune().gemm_big_t &&
           (long)((ntiles + rgt - 1) / rgt) * tblocks * splits(BIG_PH) >= 128;
   g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);  // provisional: the shape decides it below
   g.split_k = splits(g.ph);
-  int shape = g_tune.gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
+  int shape = tune().gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : 3;
   // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
   // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
-  if (shape == 1 && g.mt >= 3 && g_tune.gemm_cfg == 0) shape = 4;
+  if (shape == 1 && g.mt >= 3 && tune().gemm_cfg == 0) shape = 4;
   // long k-range per workgroup: four k-parts (8 wavefronts) keep twice the loads in flight
   // per compute unit (128 rows: QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us); the output
   // projection's 64 k-steps per split are too short for it (128 rows: 17.3 against 18.0 us;
   // 64 rows: 12.9 against 13.7 us)
-  if (shape == 3 && g_tune.gemm_cfg == 0 && (n_in >> 4) / g.split_k >= 128) shape = 2;
+  if (shape == 3 && tune().gemm_cfg == 0 && (n_in >> 4) / g.split_k >= 128) shape = 2;
   // few row tiles (the QKV projection of a grouped-query model: 192): one row tile per
   // workgroup and eight k-parts, so that the launch still has a workgroup on most compute
   // units (one compute unit pulls at most ~48 GB/s): 22.8 -> 20.2 us for 6144 x 4096
-  if (shape == 2 && g_tune.gemm_cfg == 0 && (long)ntiles * g.split_k * tblocks <= 256) shape = 5;
+  if (shape == 2 && tune().gemm_cfg == 0 && (long)ntiles * g.split_k * tblocks <= 256) shape = 5;
   g.rt = (shape == 1 || shape == 4) ? 4 : (shape == 5 ? 1 : 2);
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : (shape == 5 ? 8 : 2));
   if (g.big) { g.rt = 4; g.kw = 1; }
@@ -536,6 +536,15 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
   return check_launch();
 }
 
+// the launch plan of a projection as six numbers (for tests and experiments): row-tile
+// columns per pass, row tiles and k-parts per workgroup, row tiles per wavefront, grid
+// k-splits, 1 if the many-rows kernel runs
+void gemm_bf16_describe_plan(int tp, int n_in, int n_out, int split_k, int32_t out[6]) {
+  GemmPlan g = plan_gemm(tp, n_in, n_out, split_k);
+  out[0] = g.mt; out[1] = g.rt; out[2] = g.kw; out[3] = g.big ? g.wt : 1; out[4] = g.split_k;
+  out[5] = g.big ? 1 : 0;
+}
+
 // number of grid splits a request for split_k really gets
 int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k) {
   return plan_gemm(tp, n_in, n_out, split_k).split_k;
@@ -546,15 +555,15 @@ int gemm_bf16_split_k(int n_out, int tp, int n_in) {
   // launch has about one workgroup (of 2 row tiles) per compute unit
   int mt = tp <= 96 ? tp / 32 : 4;
   int groups = ((n_out / 32 + 1) / 2) * (tp / (32 * mt));
-  if (mt == 4 && g_tune.gemm_big_t > 0 && tp >= g_tune.gemm_big_t)
+  if (mt == 4 && tune().gemm_big_t > 0 && tp >= tune().gemm_big_t)
     groups = ((n_out / 32 + 7) / 8) * (tp / 128);  // 8 row tiles per workgroup there
   // up to 64 token rows twice as many splits pay: the launch then takes the (4 row tiles,
   // 1 k-part) shape, whose workgroups re-read half as much of the activations (down
   // 21.8 -> 20.2 us, output projection 10.8 -> 10.3 us, the sum over 8 partials instead of
   // 4 costs 0.3 us; step -1.3 % at 1..64 rows, +1 % at 96, +4 % at 128 rows)
-  const int target = tp <= 64 ? 2 * g_tune.gemm_target_wgs : g_tune.gemm_target_wgs;
+  const int target = tp <= 64 ? 2 * tune().gemm_target_wgs : tune().gemm_target_wgs;
   int sk = (target + groups - 1) / groups;
-  if (sk > g_tune.max_split_k) sk = g_tune.max_split_k;
+  if (sk > tune().max_split_k) sk = tune().max_split_k;
   return gemm_bf16_clamp_split(n_out, tp, n_in, sk);
 }
 

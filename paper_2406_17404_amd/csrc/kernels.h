@@ -15,7 +15,16 @@ struct Tunables {
   int attn_xchg_min_blocks = 48;  // blocks per workgroup from which wavefront pairs split their loads
   int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
 };
-extern Tunables g_tune;
+// trj_set_tunable writes the process-wide set; every entry point copies it once on entry
+// (TuneScope) and every launch plan of that call, on that thread, reads the copy, so the
+// workspace a call carves and the launches it makes always come from the same values.
+const Tunables& tune();
+struct TuneScope {
+  Tunables snap;
+  const Tunables* prev;
+  TuneScope();
+  ~TuneScope();
+};
 
 // per-kernel timing hooks (api.hip): when kernel class `cls` is being profiled, a HIP
 // event is recorded on the stream before and after the launch
@@ -84,6 +93,7 @@ int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_la
 // gemm_bf16.hip
 int gemm_bf16_split_k(int n_out, int tp, int n_in);
 int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k);
+void gemm_bf16_describe_plan(int tp, int n_in, int n_out, int split_k, int32_t out[6]);
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
                           int n_out, int split_k, float* y, hipStream_t st);
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,

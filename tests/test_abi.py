@@ -1,6 +1,7 @@
-"""The C-ABI library builds, loads without a GPU and exports every function that
-include/trjacobi.h declares; the Python binding knows the same names."""
+"""The C-ABI library builds, loads without a GPU and exports every function that the
+headers under include/ declare; the Python binding knows the same names."""
 import ctypes
+import glob
 import os
 import re
 
@@ -10,7 +11,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared():
-    text = open(os.path.join(ROOT, "include", "trjacobi.h")).read()
+    text = "\n".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"^(?:int32_t|uint64_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)))
 
@@ -19,6 +20,10 @@ def test_header_declares_the_four_entry_points():
     names = declared()
     for n in ("tr_verify_step", "tree_attention", "accept_path", "kv_compact"):
         assert n in names
+    # the method's header carries no experiment knobs or measurement aids
+    main = open(os.path.join(ROOT, "include", "trjacobi.h")).read()
+    for n in ("trj_set_tunable", "trj_profile_begin", "trj_copy_probe", "trj_linear"):
+        assert n not in main
 
 
 def test_library_exports_every_declared_symbol():
@@ -43,6 +48,11 @@ def test_version_and_host_side_errors_need_no_gpu():
     assert l.trj_workspace_bytes(ctypes.byref(d), 15, 1, 143, ctypes.byref(n)) == -3
     d.dtype, d.d_model = b.BF16, 250
     assert l.trj_workspace_bytes(ctypes.byref(d), 15, 1, 143, ctypes.byref(n)) == -2
+    # output widths that are not whole 32-row weight tiles are refused up front, in both modes
+    for dt in (b.BF16, b.F32):
+        for dm, ff in ((48, 1024), (256, 1040)):
+            bad = b.ModelDesc(2, dm, 4, 64, ff, 2048, 1e-5, 1e4, dt)
+            assert l.trj_workspace_bytes(ctypes.byref(bad), 15, 1, 143, ctypes.byref(n)) == -2, (dt, dm, ff)
     assert l.trj_tree_mask(None, None, 1, 1, None, None, None, None) == -1
     assert l.accept_path(None, 1, 1, 1, 1, 1000, 8, 1, 1, 1, 1, 1, 1, None) == -4
     assert l.kv_compact(None, None, 0, None, None, None, None, 1, 1, 1, 64, 64, 0, None, None) == -1

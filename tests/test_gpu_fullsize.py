@@ -5,11 +5,17 @@ benchmark times.  The oracle cannot run a 32-layer 7B step in a test's time, so:
     products of the same bf16 weights and activations);
   * tree attention is checked at the sweep sizes (L up to 8192, N up to 128, 32 heads of
     128) on all rows of sampled heads;
-  * one full-width decoder layer + LM head (d 4096, FFN 11008, 32x128 heads, prefix 1024,
-    64-node tree) is checked end to end against the oracle;
-  * the 32-layer model is checked through properties that hold at any size: determinism,
-    untouched prefix, accept/path consistent with the oracle run on the GPU's own logits,
-    and a compaction that must move a row bit-exactly.
+  * one full-width decoder layer + LM head (d 4096, FFN 11008, 32x128 heads) is checked end
+    to end against the oracle at each workload's row count, so that every kernel
+    instantiation the benchmark's workloads run is compared: prefix 1024 with a 64-node
+    tree, prefix 4096 with the 128-node tree, and a packed batch of 16 x 64 rows (the
+    many-rows projection kernel with the fused QKV and gate/up epilogues; the launch plan
+    is asked which kernel runs);
+  * the whole 32-layer 7B workload (prefix 1024, 64-node tree, seeded numpy weights drawn
+    layer by layer) is compared with the oracle: logits, and every layer's K/V rows;
+  * the 32-layer model is also checked through properties that hold at any size:
+    determinism, untouched prefix, accept/path consistent with the oracle run on the GPU's
+    own logits, and a compaction that must move a row bit-exactly.
 
 Large weights are drawn on the device with a seeded torch generator (the numpy generator
 would take minutes for 6.6e9 values); both sides consume the same values."""
@@ -159,6 +165,80 @@ def test_full_width_layer_against_oracle():
     new_len = O.kv_compact(kv, path, a, L)
     Kg, Vg = read_pool(res["k_pool"], res["v_pool"], 0, batch, 0, new_len, 128)
     assert rel_err(Kg, kv[0][0][:, :new_len]) <= 1e-2 and rel_err(Vg, kv[0][1][:, :new_len]) <= 1e-2
+
+
+def full_width_case(trees, Ls, seed, vocab=4096):
+    """One decoder layer of the 7B shape + LM head (vocab cut, the full LM-head shapes are
+    in the sampled projection test) on a batch of trees: logits, integer outputs and the
+    K/V the layer wrote, every sequence against the oracle."""
+    shape = I.ModelShape(1, 4096, 32, 128, 11008, vocab, "bf16")
+    say("generating one full-width layer on the host")
+    w = I.gen_weights(shape, seed)
+    toks = [I.gen_tokens(shape.vocab, len(t), seed, "tree", s) for s, t in enumerate(trees)]
+    pkvs = [[I.gen_prefix_kv(shape, seed, 0, s, L)] for s, L in enumerate(Ls)]
+    desc, dw = device_weights(shape, w)
+    batch = Batch(trees, Ls, toks)
+    kp, vp = nan_pool(1, 32, batch.s_pool, 128, "bf16"), nan_pool(1, 32, batch.s_pool, 128, "bf16")
+    for s in range(batch.B):
+        fill_pool(kp, vp, 0, batch, s, *pkvs[s][0])
+    say(f"running the HIP step: {batch.B} sequences, {batch.T} rows")
+    res = run_step(shape, desc, dw, batch, kp, vp)
+    assert (res["status"] == 0).all()
+    # the oracle reads fp64 copies made once (its own conversion then costs nothing)
+    w64 = dict(w, layers=[{k: np.asarray(v, np.float64) for k, v in w["layers"][0].items()}],
+               w_lm=np.asarray(w["w_lm"], np.float64), embed=np.asarray(w["embed"], np.float64))
+    worst = 0.0
+    for s in range(batch.B):
+        L, n, r = Ls[s], len(trees[s]), batch.rows(s)
+        kv = oracle_cache(shape, pkvs[s], L, n)
+        want = O.decoder_tree_forward(shape, w64, kv, toks[s], trees[s], L)
+        err = rel_err(res["logits"][r], want)
+        say(f"  sequence {s}: prefix {L}, {n} rows, logits rel err {err:.2e}")
+        assert err <= 1e-2, (s, err)
+        worst = max(worst, err)
+        am = O.greedy_argmax(res["logits"][r])
+        a, best, path, bonus = O.accept_path(am, toks[s], trees[s])
+        assert np.array_equal(res["argmax"][r], am)
+        assert (res["accept_len"][s], res["best"][s], res["bonus"][s]) == (a, best, bonus)
+        O.kv_compact(kv, path, a, L)
+        # all tree rows (the accepted ones moved up, the others where the layer wrote them)
+        Kg, Vg = read_pool(res["k_pool"], res["v_pool"], 0, batch, s, L + n, 128)
+        assert rel_err(Kg, kv[0][0]) <= 1e-2 and rel_err(Vg, kv[0][1]) <= 1e-2, s
+        assert np.array_equal(Kg[:, :L], pkvs[s][0][0]) and np.array_equal(Vg[:, :L], pkvs[s][0][1])
+    return worst
+
+
+def test_full_width_layer_long_prefix_128_rows():
+    """The code-model workload's row count and prefix at full width: 128-node tree (chain of
+    16 + retrieval branches), prefix 4096.  These are the projection instantiations that
+    workload runs (four token tiles per pass; QKV with four k-parts, gate/up with two)."""
+    d, F = 4096, 11008
+    qkv, gu = b.trj_dev_gemm_plan(128, d, 3 * d, True), b.trj_dev_gemm_plan(128, d, 2 * F, True)
+    say(f"plans at 128 rows: qkv {qkv}, gate/up {gu}")
+    assert (qkv["token_tiles"], qkv["row_tiles"], qkv["k_parts"], qkv["many_rows"]) == (4, 2, 4, 0)
+    assert (gu["token_tiles"], gu["row_tiles"], gu["k_parts"], gu["many_rows"]) == (4, 4, 2, 0)
+    tree = I.gen_trees(I.workload("C3"))[0]
+    err = full_width_case([tree], [4096], 1003)
+    say(f"full-width layer, prefix 4096, 128 rows: logits rel err {err:.2e}")
+
+
+def test_full_width_layer_packed_1024_rows_many_rows_kernel():
+    """The packed workload's row count at full width: 16 sequences of 64-node random trees,
+    1024 rows in one launch (ragged prefixes kept short so that the oracle's attention stays
+    quick; the packed attention at the workload's own prefixes has its own test above).
+    Every projection must take the many-rows kernel here, the fused QKV and gate/up
+    epilogues included."""
+    d, F = 4096, 11008
+    for name, n_in, n_out, fused in (("qkv", d, 3 * d, True), ("gate_up", d, 2 * F, True),
+                                     ("o", d, d, False), ("down", F, d, False)):
+        plan = b.trj_dev_gemm_plan(1024, n_in, n_out, fused)
+        say(f"plan at 1024 rows, {name}: {plan}")
+        assert plan["many_rows"] == 1 and plan["tiles_per_wave"] in (2, 4), name
+    rng = np.random.default_rng(1004)
+    trees = [I.tree_random(64, rng) for _ in range(16)]
+    Ls = [int(v) for v in rng.integers(64, 513, size=16)]
+    err = full_width_case(trees, Ls, 1004)
+    say(f"full-width layer, 16 x 64 rows packed: worst logits rel err {err:.2e}")
 
 
 class Full7B:

@@ -253,6 +253,18 @@ def test_host_side_errors():
     with pytest.raises(b.TrjError) as e:
         b.tr_verify_step(*args(t, mss=100))
     assert e.value.status == -2
+    # widths that are not whole weight tiles are refused before anything is enqueued, in
+    # both modes (the output buffers keep their contents)
+    marker = torch.full((256,), 77, dtype=torch.int32, device="cuda")
+    for code in (b.BF16, b.F32):
+        for d_model, d_ffn in ((48, 1408), (512, 1424)):
+            bad = b.ModelDesc(2, d_model, 4, 128, d_ffn, 1024, 1e-5, 1e4, code)
+            with pytest.raises(b.TrjError) as e:
+                b.tr_verify_step(bad, dw.struct, t, t, 4 * 64 * 128, 64, t, t, t, t, t, 1, 15, 55, t, None,
+                                 marker, marker, marker, marker, marker, marker, marker)
+            assert e.value.status == -2
+    torch.cuda.synchronize()
+    assert int((marker != 77).sum().cpu()) == 0
 
 
 def test_step_can_be_captured_in_a_graph_and_replayed():
