@@ -16,7 +16,8 @@
  *    Nothing throws, nothing aborts.
  *  - Pointers are DEVICE pointers unless the name starts with h_ (host).  The caller
  *    owns every buffer; the library allocates and frees nothing.  Process-wide state: the
- *    last HIP error code, and what the development header trjacobi_dev.h adds (launch
+ *    last HIP error code, the fixed scratch array of tree_attention_static_scratch and
+ *    its per-device address, and what the development header trjacobi_dev.h adds (launch
  *    knobs, an event timer).  Entry points may be called from several threads as long as
  *    their buffers do not overlap.
  *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL
@@ -164,6 +165,27 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
  * trj_workspace_bytes reports for a model with these heads). */
 int32_t tree_attention_workspace_bytes(int32_t B, int32_t T, int32_t n_heads, int32_t head_dim,
                                        int32_t max_seq_slots, int32_t dtype, size_t* h_bytes);
+
+/* tree_attention for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same kernels and results, with the scratch in a fixed array of
+ * TRJ_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on holds one
+ * copy until the process ends).  A call for which tree_attention_workspace_bytes reports
+ * more than that returns TRJ_ERR_WORKSPACE_TOO_SMALL and does nothing (the need is the
+ * partial sums of sequences whose keys are split over several workgroups: 8 to 17 MiB for
+ * one to four sequences with 32 heads of 128 at any length, little for larger batches;
+ * more only when a development knob asks for more splits).  No
+ * hipMalloc, hipFree or other allocating call is made.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race;
+ * calls on one stream are ordered and safe.  Nothing in the array needs clearing between
+ * calls: every call rewrites what it reads. */
+#define TRJ_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t tree_attention_static_scratch(const void* q, const void* k_layer, const void* v_layer,
+                                      const int32_t* parent, const int32_t* node_off,
+                                      const int32_t* kv_off, const int32_t* prefix_len, int32_t B,
+                                      int32_t T, int32_t n_heads, int32_t n_kv_heads,
+                                      int32_t head_dim, int32_t s_pool, int32_t max_seq_slots,
+                                      int32_t dtype, float scale, void* out, void* stream);
 
 /* Greedy argmax (Eq. 1) and the longest accepted path (section "TR-Jacobi Decoding").
  * If logits != NULL: argmax_out[i] = lowest index of the row maximum of logits[i][0..V)

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libtrjacobi.so")
 
 N_MAX = 128
 KV_BLOCK = 32
+STATIC_SCRATCH_BYTES = 32 << 20
 F32, BF16 = 0, 1
 PACK_PLAIN, PACK_QKV, PACK_GATE_UP = 0, 1, 2
 STATUS = {0: "TRJ_OK", -1: "TRJ_ERR_NULLPTR", -2: "TRJ_ERR_BAD_SHAPE", -3: "TRJ_ERR_BAD_DTYPE",
@@ -76,6 +77,7 @@ _SIGS = {
     "trj_tree_mask": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
     "tree_attention": (_i32, [_vp] * 7 + [_i32] * 8 + [_f, _vp, _sz, _vp, _vp]),
     "tree_attention_workspace_bytes": (_i32, [_i32] * 6 + [C.POINTER(_sz)]),
+    "tree_attention_static_scratch": (_i32, [_vp] * 7 + [_i32] * 8 + [_f, _vp, _vp]),
     "accept_path": (_i32, [_vp] * 4 + [_i32] * 3 + [_vp] * 7),
     "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
     "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
@@ -229,6 +231,15 @@ def tree_attention_workspace_bytes(B, T, n_heads, head_dim, max_seq_slots, dtype
     _check("tree_attention_workspace_bytes", lib().tree_attention_workspace_bytes(
         B, T, n_heads, head_dim, max_seq_slots, dtype, C.byref(n)))
     return int(n.value)
+
+
+def tree_attention_static_scratch(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T,
+                                  n_heads, head_dim, s_pool, max_seq_slots, dtype, scale, out,
+                                  n_kv_heads=0):
+    _check("tree_attention_static_scratch", lib().tree_attention_static_scratch(
+        _ptr(q), _ptr(k_layer), _ptr(v_layer), _ptr(parent), _ptr(node_off), _ptr(kv_off),
+        _ptr(prefix_len), B, T, n_heads, n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale,
+        _ptr(out), _stream()))
 
 
 def accept_path(logits, tok, parent, node_off, B, T, V, argmax_out, accept_len, best_node, path,

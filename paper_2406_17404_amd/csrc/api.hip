@@ -346,6 +346,32 @@ int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B,
                           nullptr, nullptr, nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
+// ---- the entry point for callers that cannot allocate: its scratch is this array.
+// In host code the array's name is only a stand-in for the symbol; the device address is
+// asked for once per device (static_scratch) and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[TRJ_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];  // per device: each GPU holds its own copy of the array
+static std::mutex g_scratch_mu;
+static int static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { trj::note_hip_error(e); return TRJ_ERR_HIP; }
+  if (dev < 0 || dev >= MAX_DEVICES) return TRJ_ERR_BAD_SHAPE;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // the current device's copy
+    if (e != hipSuccess || !p) {
+      trj::note_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      return TRJ_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return TRJ_OK;
+}
+
 static int tree_attention_impl(const void* q, const void* k_layer, const void* v_layer,
                        const int32_t* parent, const int32_t* node_off, const int32_t* kv_off,
                        const int32_t* prefix_len, int32_t B, int32_t T, int32_t n_heads,
@@ -365,7 +391,14 @@ static int tree_attention_impl(const void* q, const void* k_layer, const void* v
     return TRJ_ERR_BAD_SHAPE;
   if (!(scale > 0.f)) return TRJ_ERR_BAD_SHAPE;
   TuneScope tune_scope;
-  if (static_ws) return TRJ_ERR_BAD_SHAPE;
+  if (static_ws) {  // sizes first: nothing is touched when the call does not fit the array
+    Carver need(nullptr);
+    TreeWs wn;
+    carve_tree(need, dtype, B, T, n_heads, head_dim, max_seq_slots, &wn);
+    if (need.off > (size_t)TRJ_STATIC_SCRATCH_BYTES) return TRJ_ERR_WORKSPACE_TOO_SMALL;
+    TRJ_TRY(static_scratch(&workspace));
+    ws_bytes = TRJ_STATIC_SCRATCH_BYTES;
+  }
   Carver c(workspace);
   TreeWs w;
   carve_tree(c, dtype, B, T, n_heads, head_dim, max_seq_slots, &w);
@@ -412,6 +445,17 @@ int32_t tree_attention(const void* q, const void* k_layer, const void* v_layer,
   return tree_attention_impl(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T, n_heads,
                              n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale, false,
                              workspace, ws_bytes, out, stream);
+}
+
+int32_t tree_attention_static_scratch(const void* q, const void* k_layer, const void* v_layer,
+                                      const int32_t* parent, const int32_t* node_off,
+                                      const int32_t* kv_off, const int32_t* prefix_len, int32_t B,
+                                      int32_t T, int32_t n_heads, int32_t n_kv_heads,
+                                      int32_t head_dim, int32_t s_pool, int32_t max_seq_slots,
+                                      int32_t dtype, float scale, void* out, void* stream) {
+  return tree_attention_impl(q, k_layer, v_layer, parent, node_off, kv_off, prefix_len, B, T, n_heads,
+                             n_kv_heads, head_dim, s_pool, max_seq_slots, dtype, scale, true,
+                             nullptr, 0, out, stream);
 }
 
 int32_t accept_path(const float* logits, const int32_t* tok, const int32_t* parent,
