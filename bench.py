@@ -20,56 +20,83 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
-# HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counters, scaled by the copy-probe
-# calibration (profiles/C1_kernel_hbm_traffic.md holds the run and the commands); workload C1
-MEASURED_TRAFFIC = {"C1": {"gemm_gate_up": 186.3e6, "gemm_qkv": 107.5e6, "tree_attn": 26.0e6,
-                           "gemm_lm": 275.0e6}}
-MFMA_BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth (8 TB/s)
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # published dense bf16 rate = 256 CUs x 2.4 GHz x 4096 flop/clk/CU
+# kernel name (as rocprofv3 prints it) of each class whose HBM traffic the counter summary lists
+TRAFFIC_KERNEL = {"gemm_gate_up": "EpiGateUp", "gemm_qkv": "EpiQKV", "tree_attn": "tree_attn_bf16_kernel"}
 
 
-def build_device_model(shape, seed, torch, b):
-    """Random-init N(0, 0.02) weights generated on the device (synthetic), packed into
-    the library's tiled layout one matrix at a time."""
-    gen = torch.Generator(device="cuda").manual_seed(seed)
-    desc = b.make_desc(shape)
-    dw = b.DeviceWeights(desc)
-    dt = torch.bfloat16
-    d, hd, F, V = shape.d_model, shape.n_heads * shape.head_dim, shape.d_ffn, shape.vocab
-    kvd = shape.kv_heads * shape.head_dim
-
-    def rnd(n_out, n_in):
-        return (torch.randn(n_out, n_in, device="cuda", dtype=torch.float32, generator=gen) * 0.02).to(dt)
-
-    ones = torch.ones(d, device="cuda", dtype=torch.float32)
-    for _ in range(shape.n_layers):
-        dw.add_layer(ones, rnd(hd + 2 * kvd, d), rnd(d, hd), ones, rnd(2 * F, d), rnd(d, F))
-    dw.set_globals(rnd(V, d), ones, rnd(V, d))
-    dw.finish()
-    torch.cuda.synchronize()
-    return desc, dw
+def measured_traffic(workload, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed counter summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, scaled by the copy-probe calibration stated there);
+    None when no summary covers it, so that a stale figure is never reported."""
+    key = TRAFFIC_KERNEL.get(kernel_class)
+    path = os.path.join(ROOT, "profiles", f"{workload}_kernel_hbm_traffic.md")
+    if key is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and key in cells[0]:
+            try:
+                return float(cells[3]) * 1e6      # column "scaled HBM MB per launch"
+            except ValueError:
+                return None
+    return None
 
 
-def gemm_bytes(T, n_in, n_out, e=2):
-    return n_out * n_in * e + T * (n_in + n_out) * e
+def peaks_report(torch, b):
+    """The constants the fractions divide by, where they come from, and what this box
+    shows next to them: what the device reports about itself, and the rates of a plain
+    read kernel and a plain copy kernel measured in this run."""
+    info = b.trj_dev_device_info()
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
 
+    def rate(fn, nbytes, reps=10):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
-def attn_bytes(L, N, H, dh, e=2, Hkv=None):
-    """K and V of every K/V head once, q in and the output out."""
-    return 2 * (L + N) * (Hkv or H) * dh * e + 2 * N * H * dh * e
+    copy_gbps = rate(lambda: b.trj_copy_probe(dst, src, n), 2 * n)
+    read_gbps = rate(lambda: b.trj_read_probe(src, n, sink), n)
+    cus, ghz = info["compute_units"], info["clock_khz"] / 1e6
+    mem_ghz, bus = info["memory_clock_khz"] / 1e6, info["memory_bus_bits"]
+    return {"hbm_peak_GBps": HBM_PEAK_GBS, "hbm_peak_source": "published MI355X HBM3E bandwidth, 8 TB/s",
+            "mfma_bf16_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+            "mfma_bf16_peak_source": "published dense rate = 256 CUs x 2.4 GHz x 4096 flop/clk/CU",
+            "device_reports": info,
+            "mfma_bf16_from_device_TFLOPs": round(cus * ghz * 4096 / 1e3, 1),
+            "hbm_from_device_GBps": round(bus / 8 * mem_ghz * 2, 1),
+            "hbm_from_device_note": "bus width / 8 x memory clock x 2 transfers per clock, from the figures "
+                                    "the device reports",
+            "read_kernel_GBps": read_gbps, "copy_kernel_GBps": copy_gbps,
+            "measured_note": "streaming read of 1 GiB, and copy of 1 GiB (read + written bytes counted), by plain "
+                             "kernels of the library in this run: what streaming reaches on this box beside "
+                             "the published peak"}
 
 
 def cpu_baseline(wl, n_sample_layers=None):
-    """The CPU oracle on a bounded sample of the same workload: a few decoder layers at full
-    shape plus the LM head, argmax, accept and compaction; the layer time is scaled to the
-    model's depth.  The sample starts with one layer and, on a fast host, is repeated with
-    as many layers (at most 8) as make about 10 s of oracle work."""
+    """The CPU oracle on the same workload.  One layer is timed first; if the whole step then
+    fits about 30 s of oracle work it is run whole (all layers, LM head, argmax, accept,
+    compaction: `kind` "oracle, whole step"), else as many layers as make about 10 s are
+    timed and the layer time is scaled to the model's depth.  Drawing 32 layers of seeded
+    weights takes minutes with numpy, so the layers of the timed model all hold the values
+    of layer 0 (the oracle converts and multiplies each of them afresh; its work does not
+    depend on the values)."""
     if n_sample_layers is None:
         first = cpu_baseline(wl, 1)
-        t_layer = first["_t_layers"]
-        more = int(min(8, 10.0 / max(t_layer, 1e-3)))
+        t_layer = first.pop("_t_layers")
+        nl = wl.shape.n_layers
+        more = nl if t_layer * nl <= 30.0 else int(min(8, 10.0 / max(t_layer, 1e-3)))
         if more <= 1:
-            first.pop("_t_layers")
             return first
         res = cpu_baseline(wl, more)
         res.pop("_t_layers")
@@ -87,12 +114,12 @@ def cpu_baseline(wl, n_sample_layers=None):
     small = replace(shape, n_layers=n_sample_layers)
     L, n = wl.prefix_len[0], wl.tree_size
     w = I.gen_global_weights(small, wl.seed)
-    w["layers"] = [I.gen_layer_weights(small, wl.seed, l) for l in range(n_sample_layers)]
+    w["layers"] = [I.gen_layer_weights(small, wl.seed, 0)] * n_sample_layers
     tree = I.gen_trees(wl)[0]
     tok = I.gen_tokens(shape.vocab, n, wl.seed, "tree")
     kv = []
+    k, v = I.gen_prefix_kv(small, wl.seed, 0, 0, L)
     for l in range(n_sample_layers):
-        k, v = I.gen_prefix_kv(small, wl.seed, l, 0, L)
         K = np.zeros((shape.kv_heads, L + n, shape.head_dim))
         V = np.zeros_like(K)
         K[:, :L], V[:, :L] = k, v
@@ -114,15 +141,20 @@ def cpu_baseline(wl, n_sample_layers=None):
     t_layers = max((t1 - t0) - t_head, 1e-9)
     t_tail = (t2 - t1) * shape.n_layers / n_sample_layers  # compaction scales with layers
     est = t_layers * shape.n_layers / n_sample_layers + t_head + t_tail
+    whole = n_sample_layers == shape.n_layers
+    if whole:
+        est = t2 - t0
     return {"_t_layers": t_layers / n_sample_layers,
-            "value": n / est, "unit": "tree tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_sample_layers} of {shape.n_layers} decoder layers at full shape + LM head, "
-                      f"argmax, accept, compaction; layer time scaled x{shape.n_layers // n_sample_layers}; "
-                      f"measured {t2 - t0:.1f} s, estimated full step {est:.1f} s"}
+            "value": n / est, "unit": "tree tokens/s", "cores": int(threads),
+            "kind": "oracle" if whole else "oracle, sampled layers scaled to depth",
+            "sample": (f"the whole step once: {shape.n_layers} decoder layers at full shape, LM head, argmax, "
+                       f"accept, compaction, {t2 - t0:.1f} s" if whole else
+                       f"{n_sample_layers} of {shape.n_layers} decoder layers at full shape + LM head, "
+                       f"argmax, accept, compaction; layer time scaled x{shape.n_layers / n_sample_layers:.1f}; "
+                       f"measured {t2 - t0:.1f} s, estimated full step {est:.1f} s")}
 
 
-ATTN_SWEEP = ((512, 16), (512, 64), (512, 128), (2048, 16), (2048, 64), (2048, 128),
-              (8192, 16), (8192, 64), (8192, 128), (32768, 64), (131072, 64))
+ATTN_SWEEP = tuple((L, N) for L in (512, 2048, 8192) for N in (16, 32, 64, 128)) + ((32768, 64), (131072, 64))
 
 
 def attn_case(b, I, torch, np, H, dh, Ls, Ns, seed):
@@ -187,6 +219,9 @@ def main():
     ap.add_argument("--attn-case", default=None, metavar="L,N",
                     help="only one size of the tree-attention sweep (prefix L, N tree nodes, 32 "
                          "heads x 128): for profiling that kernel alone")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run the library's copy kernel on 1 GiB five times: the yardstick a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run is scaled by")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="launch-shape knob for experiments (see trj_set_tunable)")
     args = ap.parse_args()
@@ -209,6 +244,16 @@ def main():
         Ls, Ns = (int(v) for v in args.attn_case.split(","))
         print(json.dumps({"tree_attn_case": attn_case(b, I, torch, np, 32, 128, Ls, Ns, 1001)}))
         return
+    if args.copy_probe:   # for a counter run: a copy of known size and nothing else
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            b.trj_copy_probe(dst, src, n)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n, "launches": 5}))
+        return
+    peaks = peaks_report(torch, b)
     wl = I.workload(args.workload)
     shape = wl.shape
     H, dh, nl = shape.n_heads, shape.head_dim, shape.n_layers
@@ -328,7 +373,7 @@ def main():
         gbps = kd.get("net_GBps", kd["GBps"])
         roof = {"kernel": dom, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
+                "traffic": measured_traffic(wl.name, dom),
                 "avg_launch_us": us, "avg_launch_us_bracketed": kd["avg_us"],
                 "alg_bytes_per_launch": kd["alg_bytes"]}
 
@@ -436,7 +481,7 @@ def main():
                                           - shape.vocab * shape.d_model * 2
                                           + nl * sum(attn_bytes(l, N, H, dh, Hkv=Hkv) for l in wl.prefix_len))
                                          / (HBM_PEAK_GBS * 1e9) * 1e3, 3),
-        "roofline": roof, "kernels": kernels, "event_pair_us": event_pair_us and round(event_pair_us, 2),
+        "roofline": roof, "peaks": peaks, "kernels": kernels, "event_pair_us": event_pair_us and round(event_pair_us, 2),
         "cpu_baseline": cpu,
         "chain_length_sweep": sweep, "decode_loop": loop, "tree_attn_sweep": attn_sweep,
         # context only (another machine, trained weights, end-to-end decoding): the paper's

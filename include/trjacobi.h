@@ -226,6 +226,39 @@ int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, v
                        int32_t* path, int32_t* bonus_tok, int32_t* new_len,
                        int32_t* status_dev, void* stream);
 
+/* ---- Static tree template (appendix "Templates for Token Tree": one fixed sparse tree is
+ * used for every verification step).  What depends on the tree alone is computed once
+ * into a caller-owned device buffer: validity, depth and ancestor bit rows of every node,
+ * and the rotary table cos/sin(p * theta^(-2j/head_dim)) for positions p = 0..max_pos-1.
+ * tr_verify_step_template is tr_verify_step with that buffer: per step only the parts
+ * that depend on the prefix lengths are recomputed (slot range checks, slot and position
+ * of every row, the attention work list), in one launch, and results are identical.
+ *  - tr_template_bytes: size of the buffer for B sequences, T rows, max_pos positions.
+ *  - tr_template_prepare: fills it from parent[T] / node_off[B+1] (same meaning as in
+ *    tr_verify_step).  A malformed tree is recorded in the buffer and marks its sequence
+ *    (status_dev[s] = 1) in every step that uses it.
+ *  - tr_verify_step_template: B, T, max_pos, the model's head_dim and node_off[] must be
+ *    those the buffer was prepared with, and parent[] must hold the same tree (it is
+ *    still read by the acceptance rule); a buffer prepared for other sizes or row
+ *    ranges marks every affected sequence malformed instead of being used.  Every
+ *    sequence needs prefix_len[s] + N_s <= max_pos, else it is marked as well.  The
+ *    buffer is only read; several steps (and streams) may share it. */
+int32_t tr_template_bytes(const trj_model_desc* desc, int32_t B, int32_t T, int32_t max_pos,
+                          size_t* h_bytes);
+int32_t tr_template_prepare(const trj_model_desc* desc, const int32_t* parent,
+                            const int32_t* node_off, int32_t B, int32_t T, int32_t max_pos,
+                            void* tmpl, size_t tmpl_bytes, void* stream);
+int32_t tr_verify_step_template(const trj_model_desc* desc, const trj_weights* weights,
+                                void* k_pool, void* v_pool, size_t kv_layer_stride, int32_t s_pool,
+                                const int32_t* tok, const int32_t* parent, const int32_t* node_off,
+                                const int32_t* kv_off, const int32_t* prefix_len, int32_t B,
+                                int32_t T, int32_t max_seq_slots, const void* tmpl,
+                                size_t tmpl_bytes, int32_t max_pos, void* workspace,
+                                size_t ws_bytes, float* logits, int32_t* argmax_out,
+                                int32_t* accept_len, int32_t* best_node, int32_t* path,
+                                int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev,
+                                void* stream);
+
 /* ---- TR-Jacobi decoding loop (section "TR-Jacobi Decoding") -------------------------
  * Generation starts from a tree whose nodes are ahead noise (Eq. 4), every round
  * verifies the tree with tr_verify_step's forward, commits the longest accepted path

@@ -70,6 +70,15 @@ int32_t trj_profile_event_overhead(int32_t pairs, float* h_avg_ms, void* stream)
  * calibrate the HBM traffic counters against a kernel whose traffic is known. */
 int32_t trj_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Measurement aid: a streaming read of `bytes` (a multiple of 16) from src and nothing else
+ * (sink: 4 bytes of device memory, written only if the data has one particular value). */
+int32_t trj_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
+/* What the current device reports (hipDeviceGetAttribute): h_info[6] (HOST) = compute
+ * units, engine clock kHz, memory clock kHz, memory bus width in bits, L2 bytes, LDS bytes
+ * per workgroup. */
+int32_t trj_dev_device_info(int32_t* h_info);
+
 #ifdef __cplusplus
 }
 #endif

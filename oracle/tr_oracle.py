@@ -119,7 +119,7 @@ def silu(z):
     return z / (1.0 + np.exp(-z))
 
 
-def tree_attention(q, k, v, parent, prefix_len, scale=None):
+def tree_attention(q, k, v, parent, prefix_len, scale=None, p_storage=None):
     """Tree-masked attention for one sequence.
 
     q[N, H, dh]; k, v[Hkv, S, dh] with S >= prefix_len + N, tree node j stored at slot
@@ -127,6 +127,10 @@ def tree_attention(q, k, v, parent, prefix_len, scale=None):
     (Hkv == H: ordinary multi-head attention).  Node i attends to slots
     0..prefix_len-1 and to prefix_len + j for every j on its root path (itself
     included).  Returns out[N, H, dh].
+
+    p_storage (optional, see decoder_tree_forward's `storage`): applied to the
+    un-normalised weights exp(s - max s) before they multiply V, while the normalising
+    sum is taken over the unrounded weights.
     """
     q = np.asarray(q, F64)
     k = np.asarray(k, F64)
@@ -143,12 +147,15 @@ def tree_attention(q, k, v, parent, prefix_len, scale=None):
         for hh in range(h):
             s = (k[hh // group, slots] @ q[i, hh]) * scale
             p = np.exp(s - s.max())
-            p /= p.sum()
-            out[i, hh] = p @ v[hh // group, slots]
+            if p_storage is None:
+                p /= p.sum()
+                out[i, hh] = p @ v[hh // group, slots]
+            else:
+                out[i, hh] = (p_storage(p) @ v[hh // group, slots]) / p.sum()
     return out
 
 
-def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=None):
+def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=None, storage=None):
     """One forward pass of the decoder over the tree's token rows (one sequence).
 
     shape: object with n_layers, d_model, n_heads, head_dim, d_ffn, vocab, rms_eps,
@@ -159,7 +166,18 @@ def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=No
     0..prefix_len-1 hold the prefix (K already rotated); this call
     writes the tree's K/V into slots prefix_len + i.  Returns logits[N, V] (fp64).
     `collect`, if a dict, receives per-layer intermediates for kernel-level tests.
+
+    `storage` (optional) models a reduced-precision mode, about which the paper says
+    nothing (it never states the inference precision): a dict name -> callable; the
+    tensors such a mode keeps in 16 bits pass through the callable where one is given:
+    "h" (both normalised activations), "q", "kv" (the tree's K after rotation and V, as
+    cached), "p" (attention weights, see tree_attention), "attn" (attention output),
+    "act" (SiLU(gate) * up).  Everything else, and everything when storage is None (the
+    default: the plain definition), stays fp64.  Tests use it to tell which rounding
+    point an observed deviation comes from.
     """
+    st = storage or {}
+    keep = lambda name, a: st[name](a) if name in st else a
     tok = np.asarray(tok)
     n = len(tok)
     L = int(prefix_len)
@@ -171,18 +189,18 @@ def decoder_tree_forward(shape, weights, kv, tok, parent, prefix_len, collect=No
     for l in range(shape.n_layers):
         w = weights["layers"][l]
         K, V = kv[l]
-        h = rmsnorm(x, w["g_attn"], shape.rms_eps)
+        h = keep("h", rmsnorm(x, w["g_attn"], shape.rms_eps))
         qkv = h @ np.asarray(w["wqkv"], F64).T
-        q = rope(qkv[:, :hd].reshape(n, H, dh), pos, shape.rope_theta)
-        kk = rope(qkv[:, hd:hd + kvd].reshape(n, Hkv, dh), pos, shape.rope_theta)
-        vv = qkv[:, hd + kvd:].reshape(n, Hkv, dh)
+        q = keep("q", rope(qkv[:, :hd].reshape(n, H, dh), pos, shape.rope_theta))
+        kk = keep("kv", rope(qkv[:, hd:hd + kvd].reshape(n, Hkv, dh), pos, shape.rope_theta))
+        vv = keep("kv", qkv[:, hd + kvd:].reshape(n, Hkv, dh))
         K[:, L:L + n] = kk.transpose(1, 0, 2)
         V[:, L:L + n] = vv.transpose(1, 0, 2)
-        o = tree_attention(q, K, V, parent, L)
+        o = keep("attn", tree_attention(q, K, V, parent, L, p_storage=st.get("p")))
         x_mid = x + o.reshape(n, hd) @ np.asarray(w["wo"], F64).T
-        h2 = rmsnorm(x_mid, w["g_ffn"], shape.rms_eps)
+        h2 = keep("h", rmsnorm(x_mid, w["g_ffn"], shape.rms_eps))
         gu = h2 @ np.asarray(w["w_gate_up"], F64).T
-        act = silu(gu[:, :F]) * gu[:, F:]
+        act = keep("act", silu(gu[:, :F]) * gu[:, F:])
         x_out = x_mid + act @ np.asarray(w["w_down"], F64).T
         if collect is not None:
             collect.setdefault("layers", []).append(

@@ -68,6 +68,8 @@ _SIGS = {
     "trj_profile_end": (_i32, [C.POINTER(C.c_float), _i32, C.POINTER(_i32)]),
     "trj_profile_event_overhead": (_i32, [_i32, C.POINTER(C.c_float), _vp]),
     "trj_copy_probe": (_i32, [_vp, _vp, _sz, _vp]),
+    "trj_read_probe": (_i32, [_vp, _sz, _vp, _vp]),
+    "trj_dev_device_info": (_i32, [_ip]),
     "trj_dev_gemm_plan": (_i32, [_i32, _i32, _i32, _i32, _ip]),
     "trj_workspace_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
     "trj_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -82,6 +84,10 @@ _SIGS = {
     "kv_compact": (_i32, [_vp, _vp, _sz] + [_vp] * 4 + [_i32] * 6 + [_vp, _vp]),
     "tr_verify_step": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
                        [_vp] * 5 + [_i32] * 3 + [_vp, _sz] + [_vp] * 9),
+    "tr_template_bytes": (_i32, [C.POINTER(ModelDesc), _i32, _i32, _i32, C.POINTER(_sz)]),
+    "tr_template_prepare": (_i32, [C.POINTER(ModelDesc), _vp, _vp, _i32, _i32, _i32, _vp, _sz, _vp]),
+    "tr_verify_step_template": (_i32, [C.POINTER(ModelDesc), C.POINTER(Weights), _vp, _vp, _sz, _i32] +
+                                [_vp] * 5 + [_i32] * 3 + [_vp, _sz, _i32, _vp, _sz] + [_vp] * 9),
     "trj_splitmix64": (C.c_uint64, [C.c_uint64, C.c_uint64]),
     "trj_ahead_noise": (_i32, [_ip, _i32, C.c_uint64, _i32, _i32, _ip]),
     "trj_prompt_lookup": (_i32, [_ip, _i32, _i32, _i32, _ip, _ip]),
@@ -179,6 +185,17 @@ def trj_copy_probe(dst, src, nbytes: int) -> None:
     _check("trj_copy_probe", lib().trj_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream()))
 
 
+def trj_read_probe(src, nbytes: int, sink) -> None:
+    _check("trj_read_probe", lib().trj_read_probe(_ptr(src), nbytes, _ptr(sink), _stream()))
+
+
+def trj_dev_device_info() -> dict:
+    out = (C.c_int32 * 6)()
+    _check("trj_dev_device_info", lib().trj_dev_device_info(out))
+    return dict(zip(("compute_units", "clock_khz", "memory_clock_khz", "memory_bus_bits", "l2_bytes",
+                     "lds_bytes_per_workgroup"), (int(v) for v in out)))
+
+
 def trj_dev_gemm_plan(T: int, n_in: int, n_out: int, fused: bool) -> dict:
     out = (C.c_int32 * 6)()
     _check("trj_dev_gemm_plan", lib().trj_dev_gemm_plan(T, n_in, n_out, int(fused), out))
@@ -265,6 +282,31 @@ def tr_verify_step(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_layer_s
         max_seq_slots, _ptr(workspace), workspace.numel() * workspace.element_size(),
         _ptr(logits), _ptr(argmax_out), _ptr(accept_len), _ptr(best_node), _ptr(path),
         _ptr(bonus_tok), _ptr(new_len), _ptr(status_dev), _stream()))
+
+
+def tr_template_bytes(desc: ModelDesc, B: int, T: int, max_pos: int) -> int:
+    n = _sz(0)
+    _check("tr_template_bytes", lib().tr_template_bytes(C.byref(desc), B, T, max_pos, C.byref(n)))
+    return int(n.value)
+
+
+def tr_template_prepare(desc: ModelDesc, parent, node_off, B, T, max_pos, tmpl) -> None:
+    _check("tr_template_prepare", lib().tr_template_prepare(
+        C.byref(desc), _ptr(parent), _ptr(node_off), B, T, max_pos, _ptr(tmpl),
+        tmpl.numel() * tmpl.element_size(), _stream()))
+
+
+def tr_verify_step_template(desc: ModelDesc, weights: Weights, k_pool, v_pool, kv_layer_stride, s_pool,
+                            tok, parent, node_off, kv_off, prefix_len, B, T, max_seq_slots, tmpl,
+                            max_pos, workspace, logits, argmax_out, accept_len, best_node, path,
+                            bonus_tok, new_len, status_dev):
+    _check("tr_verify_step_template", lib().tr_verify_step_template(
+        C.byref(desc), C.byref(weights), _ptr(k_pool), _ptr(v_pool), kv_layer_stride, s_pool,
+        _ptr(tok), _ptr(parent), _ptr(node_off), _ptr(kv_off), _ptr(prefix_len), B, T,
+        max_seq_slots, _ptr(tmpl), tmpl.numel() * tmpl.element_size(), max_pos, _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _ptr(logits), _ptr(argmax_out),
+        _ptr(accept_len), _ptr(best_node), _ptr(path), _ptr(bonus_tok), _ptr(new_len),
+        _ptr(status_dev), _stream()))
 
 
 # ------------------------------------------------------------------ decoding loop

@@ -337,6 +337,47 @@ int32_t trj_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
   return check_launch();
 }
 
+// Streaming read of a buffer (loads with the streaming hint, nothing stored unless the data
+// has one particular value): what a kernel that only reads reaches on this device.
+__global__ __launch_bounds__(512) void read_probe_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                         uint32_t* __restrict__ sink) {
+  u32x4 acc = {0, 0, 0, 0};
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1;
+}
+int32_t trj_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return TRJ_ERR_NULLPTR;
+  if (bytes == 0 || (bytes & 15)) return TRJ_ERR_BAD_SHAPE;
+  read_probe_kernel<<<2048, 512, 0, (hipStream_t)stream>>>((const u32x4*)src, bytes / 16, (uint32_t*)sink);
+  return check_launch();
+}
+
+// What the current device reports about itself (for the peaks a benchmark divides by).
+int32_t trj_dev_device_info(int32_t* h_info) {
+  if (!h_info) return TRJ_ERR_NULLPTR;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  const hipDeviceAttribute_t attr[6] = {hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate,
+                                        hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth,
+                                        hipDeviceAttributeL2CacheSize, hipDeviceAttributeMaxSharedMemoryPerBlock};
+  for (int i = 0; i < 6 && e == hipSuccess; ++i) {
+    int v = 0;
+    e = hipDeviceGetAttribute(&v, attr[i], dev);
+    h_info[i] = v;
+  }
+  if (e != hipSuccess) { note_hip_error(e); return TRJ_ERR_HIP; }
+  return TRJ_OK;
+}
+
 int32_t trj_tree_mask(const int32_t* parent, const int32_t* node_off, int32_t B, int32_t T,
                       int32_t* depth, uint64_t* anc, int32_t* status_dev, void* stream) {
   if (!parent || !node_off || !depth || !anc || !status_dev) return TRJ_ERR_NULLPTR;
@@ -538,7 +579,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
               int32_t B, int32_t T, int32_t max_seq_slots, void* workspace, size_t ws_bytes,
               float* logits, int32_t* argmax_out, int32_t* accept_len, int32_t* best_node,
               int32_t* path, int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev,
-              bool with_head, hipStream_t st) {
+              bool with_head, hipStream_t st, const TemplateView* tmpl, int max_pos) {
   TRJ_TRY(check_desc(desc));
   if (!weights || !weights->h_layers || !weights->embed || !weights->g_final || !weights->w_lm ||
       !k_pool || !v_pool || !tok || !parent || !node_off || !kv_off || !prefix_len || !workspace ||
@@ -570,25 +611,43 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
 
   // bf16: the attention output's padding rows and rows of malformed sequences stay zero all step
   const bool bf16 = m.dtype == TRJ_BF16;
-  TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots,
-                           w.t.depth, w.t.anc, status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq,
-                           bf16 ? w.op : nullptr, bf16 ? (size_t)padded_rows(T) * hd * 2 : 0, st));
-  TRJ_TRY(launch_rope_table(w.t.row_pos, T, dh, m.rope_theta, w.cs, st));
-  TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
+  void* zero = bf16 ? w.op : nullptr;
+  const size_t zero_bytes = bf16 ? (size_t)padded_rows(T) * hd * 2 : 0;
+  // rotary table: one row per tree row, or (with a prepared template) one row per position,
+  // found through each row's position
+  const float2* cs = w.cs;
+  const int32_t* cs_row = nullptr;
+  if (tmpl) {
+    // what depends on the tree alone comes from the template; one launch does the rest
+    TRJ_TRY(launch_template_step_prep(*tmpl, node_off, kv_off, prefix_len, B, T, dh, max_pos, s_pool,
+                                      max_seq_slots, status_dev, w.t.row_slot, w.t.row_pos,
+                                      w.t.row_seq, w.t.attn_rows, w.t.attn_qg, w.t.attn_bpwg,
+                                      w.t.attn_ns, bf16 ? w.t.items : nullptr, zero, zero_bytes, st));
+    w.t.depth = tmpl->depth;
+    w.t.anc = tmpl->anc;
+    cs = tmpl->cs;
+    cs_row = w.t.row_pos;
+  } else {
+    TRJ_TRY(launch_tree_prep(parent, node_off, kv_off, prefix_len, B, T, s_pool, max_seq_slots,
+                             w.t.depth, w.t.anc, status_dev, w.t.row_slot, w.t.row_pos, w.t.row_seq,
+                             zero, zero_bytes, st));
+    TRJ_TRY(launch_rope_table(w.t.row_pos, T, dh, m.rope_theta, w.cs, st));
+    if (bf16)
+      TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg,
+                                w.t.attn_bpwg, w.t.attn_ns, w.t.items, st));
+  }
 
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
-    TRJ_TRY(launch_attn_items(node_off, prefix_len, kv_off, status_dev, B, w.t.attn_rows, w.t.attn_qg,
-                              w.t.attn_bpwg, w.t.attn_ns, w.t.items, st));
-    { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(nullptr, 0, w.x, weights->h_layers[0].g_attn, T, d, tp, m.rms_eps,
-                               w.hp, st)); }
+    { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_embed_norm((const uint16_t*)weights->embed, tok, T, d, V, w.x,
+                              weights->h_layers[0].g_attn, tp, m.rms_eps, w.hp, st)); }
     for (int l = 0; l < m.n_layers; ++l) {
       const trj_layer_weights& lw = weights->h_layers[l];
       uint16_t* kl = (uint16_t*)k_pool + (size_t)l * kv_layer_stride;
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
-      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, w.cs,
-                              w.t.row_slot, w.q, kl, vl, st)); }
+      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, cs,
+                              cs_row, w.t.row_slot, w.q, kl, vl, st)); }
       TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, node_off, kv_off, prefix_len, status_dev,
                                     w.t.items, B, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
                                     w.op, st));
@@ -603,13 +662,14 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
     if (!with_head) return TRJ_OK;
     { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st)); }
   } else {
+    TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
     for (int l = 0; l < m.n_layers; ++l) {
       const trj_layer_weights& lw = weights->h_layers[l];
       float* kl = (float*)k_pool + (size_t)l * kv_layer_stride;
       float* vl = (float*)v_pool + (size_t)l * kv_layer_stride;
       TRJ_TRY(launch_rmsnorm_f32(w.x, lw.g_attn, T, d, m.rms_eps, w.h, st));
       TRJ_TRY(launch_gemm_f32(w.h, (const float*)lw.wqkv, T, d, (H + 2 * Hkv) * dh, 0, w.qkv, st));
-      TRJ_TRY(launch_rope_kv_f32(w.qkv, w.cs, w.t.row_slot, T, H, Hkv, dh, s_pool, w.qf, kl, vl, st));
+      TRJ_TRY(launch_rope_kv_f32(w.qkv, cs, cs_row, w.t.row_slot, T, H, Hkv, dh, s_pool, w.qf, kl, vl, st));
       TRJ_TRY(launch_tree_attn_f32(w.qf, kl, vl, w.t.anc, w.t.row_seq, node_off, kv_off, prefix_len,
                                    status_dev, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.of, st));
       TRJ_TRY(launch_gemm_f32(w.of, (const float*)lw.wo, T, hd, d, 1, w.x, st));
@@ -639,7 +699,65 @@ size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_s
   return c.off + 256;
 }
 int check_model(const trj_model_desc* m) { return check_desc(m); }
+
+// layout of a template buffer; with base == nullptr it only measures
+size_t template_carve(void* base, int B, int T, int dh, int max_pos, TemplateView* v) {
+  Carver c(base);
+  v->hdr = c.take<int32_t>(8);
+  v->depth = c.take<int32_t>(T);
+  v->anc = c.take<uint64_t>(2 * (size_t)T);
+  v->tstatus = c.take<int32_t>(B);
+  v->tnoff = c.take<int32_t>((size_t)B + 1);
+  v->tseq = c.take<int32_t>(T);
+  v->cs = c.take<float2>((size_t)max_pos * (dh / 2));
+  return align_up(c.off, 256);
+}
+static int check_template_args(const trj_model_desc* desc, int B, int T, int max_pos) {
+  TRJ_TRY(check_desc(desc));
+  if (B < 1 || T < B || max_pos < 1 || max_pos > (1 << 24)) return TRJ_ERR_BAD_SHAPE;
+  if ((long)T > (long)B * TRJ_N_MAX) return TRJ_ERR_TREE_TOO_LARGE;
+  return TRJ_OK;
+}
 }  // namespace trj
+
+extern "C" int32_t tr_template_bytes(const trj_model_desc* desc, int32_t B, int32_t T, int32_t max_pos,
+                                     size_t* h_bytes) {
+  if (!h_bytes) return TRJ_ERR_NULLPTR;
+  TRJ_TRY(trj::check_template_args(desc, B, T, max_pos));
+  trj::TemplateView v;
+  *h_bytes = trj::template_carve(nullptr, B, T, desc->head_dim, max_pos, &v);
+  return TRJ_OK;
+}
+
+extern "C" int32_t tr_template_prepare(const trj_model_desc* desc, const int32_t* parent,
+                                       const int32_t* node_off, int32_t B, int32_t T, int32_t max_pos,
+                                       void* tmpl, size_t tmpl_bytes, void* stream) {
+  if (!parent || !node_off || !tmpl) return TRJ_ERR_NULLPTR;
+  TRJ_TRY(trj::check_template_args(desc, B, T, max_pos));
+  trj::TemplateView v;
+  if (trj::template_carve(tmpl, B, T, desc->head_dim, max_pos, &v) > tmpl_bytes)
+    return TRJ_ERR_WORKSPACE_TOO_SMALL;
+  return trj::launch_template_prepare(parent, node_off, B, T, desc->head_dim, max_pos, desc->rope_theta,
+                                      v, (hipStream_t)stream);
+}
+
+extern "C" int32_t tr_verify_step_template(
+    const trj_model_desc* desc, const trj_weights* weights, void* k_pool, void* v_pool,
+    size_t kv_layer_stride, int32_t s_pool, const int32_t* tok, const int32_t* parent,
+    const int32_t* node_off, const int32_t* kv_off, const int32_t* prefix_len, int32_t B, int32_t T,
+    int32_t max_seq_slots, const void* tmpl, size_t tmpl_bytes, int32_t max_pos, void* workspace,
+    size_t ws_bytes, float* logits, int32_t* argmax_out, int32_t* accept_len, int32_t* best_node,
+    int32_t* path, int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev, void* stream) {
+  if (!tmpl) return TRJ_ERR_NULLPTR;
+  TRJ_TRY(trj::check_template_args(desc, B, T, max_pos));
+  trj::TemplateView v;
+  if (trj::template_carve(const_cast<void*>(tmpl), B, T, desc->head_dim, max_pos, &v) > tmpl_bytes)
+    return TRJ_ERR_WORKSPACE_TOO_SMALL;
+  return trj::step_impl(desc, weights, k_pool, v_pool, kv_layer_stride, s_pool, tok, parent, node_off,
+                        kv_off, prefix_len, B, T, max_seq_slots, workspace, ws_bytes, logits,
+                        argmax_out, accept_len, best_node, path, bonus_tok, new_len, status_dev,
+                        true, (hipStream_t)stream, &v, max_pos);
+}
 
 extern "C" int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
                        void* v_pool, size_t kv_layer_stride, int32_t s_pool, const int32_t* tok,

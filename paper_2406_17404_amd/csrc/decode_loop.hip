@@ -210,7 +210,8 @@ int32_t tr_jacobi_generate_workspace_bytes(const trj_model_desc* desc, int32_t n
     }
     if (bound >= cap || bound >= s_pool) break;
   }
-  *h_bytes = align_up(need + loop_fixed_bytes(), 256);
+  TemplateView tv;  // the rounds verify with one prepared template over cap positions
+  *h_bytes = align_up(need + loop_fixed_bytes() + template_carve(nullptr, 1, n_nodes, desc->head_dim, cap, &tv), 256);
   return TRJ_OK;
 }
 
@@ -245,8 +246,14 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
   base += align_up(sizeof(LoopConst), 256);
   PrefillBlock* d_pf = reinterpret_cast<PrefillBlock*>(base);
   base += align_up(sizeof(PrefillBlock), 256);
+  // the template of the decoding rounds: the tree is the same in every round (appendix
+  // "Templates for Token Tree"), so its bookkeeping and the rotary table are made once
+  const int max_pos = prompt_len + max_new + N;
+  TemplateView tv;
+  const size_t tmpl_bytes = template_carve(base, 1, N, desc->head_dim, max_pos, &tv);
+  base += tmpl_bytes;
   void* step_ws = base;
-  const size_t step_ws_bytes = ws_bytes - loop_fixed_bytes();
+  const size_t step_ws_bytes = ws_bytes - loop_fixed_bytes() - tmpl_bytes;
 
   LoopIn h_in{};
   LoopOut h_out{};
@@ -293,6 +300,8 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
   h_c.node_off[0] = 0;
   h_c.node_off[1] = N;
   TRJ_HIP(hipMemcpyAsync(d_tree, &h_c, sizeof(h_c), hipMemcpyHostToDevice, st));
+  TRJ_TRY(launch_template_prepare(d_tree->parent, d_tree->node_off, 1, N, desc->head_dim, max_pos,
+                                  desc->rope_theta, tv, st));
   TRJ_HIP(hipStreamSynchronize(st));
 
   std::vector<int32_t> ctx(h_prompt, h_prompt + prompt_len);
@@ -308,7 +317,7 @@ int32_t tr_jacobi_generate(const trj_model_desc* desc, const trj_weights* weight
                       d_tree->parent, d_tree->node_off, &d_tree->kv_off, &d_in->prefix_len, 1, N,
                       slot_bound(L + N, s_pool), step_ws, step_ws_bytes, nullptr, d_out->argmax,
                       &d_out->accept_len, &d_out->best, d_out->path, &d_out->bonus, &d_out->new_len,
-                      &d_out->status, true, st));
+                      &d_out->status, true, st, &tv, max_pos));
     TRJ_HIP(hipMemcpyAsync(&h_out, d_out, sizeof(h_out), hipMemcpyDeviceToHost, st));
     TRJ_HIP(hipStreamSynchronize(st));
     if (h_out.status != 0 || h_out.accept_len < 0 || h_out.accept_len >= N) return TRJ_ERR_BAD_SHAPE;

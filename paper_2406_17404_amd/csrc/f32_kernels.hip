@@ -22,14 +22,15 @@ __device__ inline int packed_row(int n, int kind, int n_out, int n_heads, int dh
 }
 
 // ------------------------------------------------------------------ rotary table
-// cs[t][j] = (cos, sin) of row_pos[t] * theta^(-2j/dh), evaluated in double.
+// cs[t][j] = (cos, sin) of row_pos[t] * theta^(-2j/dh), evaluated in double; without
+// row_pos the table is over positions themselves (row t = position t).
 __global__ void rope_table_kernel(const int32_t* __restrict__ row_pos, int T, int dh, float theta,
                                   float2* __restrict__ cs) {
   int half = dh >> 1;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= T * half) return;
   int t = idx / half, j = idx % half;
-  double ang = (double)row_pos[t] * pow((double)theta, -2.0 * j / dh);
+  double ang = (double)(row_pos ? row_pos[t] : t) * pow((double)theta, -2.0 * j / dh);
   cs[idx] = make_float2((float)cos(ang), (float)sin(ang));
 }
 int launch_rope_table(const int32_t* row_pos, int T, int dh, float theta, float2* cs,
@@ -140,6 +141,7 @@ int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, 
 // qkv[t][packed rows] -> q[t][head][c] (rotated), K (rotated) and V into the pool at the
 // row's slot.  One block per row, one thread per (head, j < dh/2).
 __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs,
+                                   const int32_t* __restrict__ cs_row,
                                    const int32_t* __restrict__ row_slot, int n_heads,
                                    int n_kv_heads, int dh, int s_pool, float* __restrict__ q,
                                    float* __restrict__ k_layer, float* __restrict__ v_layer) {
@@ -148,9 +150,10 @@ __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* 
   const float* y = qkv + (size_t)t * n_out;
   const int slot = row_slot[t];
   if (slot < 0) return;  // row of a malformed sequence
+  const size_t cbase = (size_t)(cs_row ? cs_row[t] : t) * half;  // table row: the row itself or its position
   for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
     int head = idx / half, j = idx % half;
-    float2 c = cs[(size_t)t * half + j];
+    float2 c = cs[cbase + j];
     int na = head * dh + j, nb = na + half;
     float qa = y[packed_row(na, TRJ_PACK_QKV, n_out, n_heads, dh)];
     float qb = y[packed_row(nb, TRJ_PACK_QKV, n_out, n_heads, dh)];
@@ -160,7 +163,7 @@ __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* 
   }
   for (int idx = threadIdx.x; idx < n_kv_heads * half; idx += blockDim.x) {
     int head = idx / half, j = idx % half;
-    float2 c = cs[(size_t)t * half + j];
+    float2 c = cs[cbase + j];
     int na = head * dh + j, nb = na + half;
     float ka = y[packed_row(hd + na, TRJ_PACK_QKV, n_out, n_heads, dh)];
     float kb = y[packed_row(hd + nb, TRJ_PACK_QKV, n_out, n_heads, dh)];
@@ -172,10 +175,11 @@ __global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, const float2* 
     vp[v_off(slot, j + half, dh)] = y[hd + kvd + nb];
   }
 }
-int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* row_slot, int T,
+int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* cs_row,
+                       const int32_t* row_slot, int T,
                        int n_heads, int n_kv_heads, int dh, int s_pool, float* q, float* k_layer,
                        float* v_layer, hipStream_t st) {
-  rope_kv_f32_kernel<<<T, 256, 0, st>>>(qkv, cs, row_slot, n_heads, n_kv_heads, dh, s_pool, q,
+  rope_kv_f32_kernel<<<T, 256, 0, st>>>(qkv, cs, cs_row, row_slot, n_heads, n_kv_heads, dh, s_pool, q,
                                         k_layer, v_layer);
   return check_launch();
 }

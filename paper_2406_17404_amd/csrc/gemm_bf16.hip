@@ -82,7 +82,8 @@ struct EpiGateUp {
 
 // ---- epilogue: rotary on q and k, q stored plain [T][H][dh], k and v into the pool.
 struct EpiQKV {
-  const float2* cs;         // [T][dh/2] cos, sin of the row's position
+  const float2* cs;         // [.][dh/2] cos, sin: row t of the table, or row cs_row[t] if given
+  const int32_t* cs_row;    // optional: the table is indexed by position, this is each row's
   const int32_t* row_slot;  // pool slot of each row, -1 = skip
   uint16_t* q;
   uint16_t* k_layer;
@@ -100,6 +101,7 @@ struct EpiQKV {
     const int head = rel / tph, jt = rel % tph;
     const int hh = lane >> 5;
     if (sec < 2) {
+      const float2* csr = cs + (size_t)(cs_row ? cs_row[t] : t) * half;
       uint16_t* plane = k_layer + (size_t)head * s_pool * dh;
       uint16_t* qrow = q + ((size_t)t * n_heads + head) * dh;
 #pragma unroll
@@ -108,7 +110,7 @@ struct EpiQKV {
         float ra[4], rb[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float2 sc = cs[(size_t)t * half + c + i];
+          float2 sc = csr[c + i];
           float a = acc[4 * g + i], b = acc[8 + 4 * g + i];
           ra[i] = a * sc.x - b * sc.y;
           rb[i] = b * sc.x + a * sc.y;
@@ -580,9 +582,10 @@ int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in,
 }
 
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* row_slot,
-                    uint16_t* q, uint16_t* k_layer, uint16_t* v_layer, hipStream_t st) {
-  EpiQKV e{cs, row_slot, q, k_layer, v_layer, T, n_heads, n_kv_heads, dh, s_pool};
+                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* cs_row,
+                    const int32_t* row_slot, uint16_t* q, uint16_t* k_layer, uint16_t* v_layer,
+                    hipStream_t st) {
+  EpiQKV e{cs, cs_row, row_slot, q, k_layer, v_layer, T, n_heads, n_kv_heads, dh, s_pool};
   return launch_gemm(xp, w, tp, n_in, (n_heads + 2 * n_kv_heads) * dh, 1, e, st);
 }
 
@@ -672,6 +675,80 @@ int launch_reduce_norm(const float* partial, int n_split, float* x, const float*
   if ((d & 7) || d > 8 * RN_THREADS * RN_MAXG) return TRJ_ERR_BAD_SHAPE;
   reduce_norm_kernel<<<tp, RN_THREADS, 0, st>>>(partial, n_split, (size_t)T * d, x, g, T, d, tp,
                                                 eps, hp);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ embedding + first RMSNorm
+// One workgroup per token row: x[t] = E[tok[t]] as fp32 (ids outside [0, vocab) are clamped)
+// and h = x * g / sqrt(mean(x^2) + eps) in the tiled activation layout; padding rows of the
+// tile are written as zeros.
+__global__ __launch_bounds__(RN_THREADS) void embed_norm_kernel(
+    const uint16_t* __restrict__ embed, const int32_t* __restrict__ tok, int T, int d, int vocab,
+    float* __restrict__ x, const float* __restrict__ g, int tp, float eps,
+    uint16_t* __restrict__ hp) {
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const int ngran = d >> 3;
+  if (t >= T) {
+    const u32x4 z = {0, 0, 0, 0};
+    for (int gi = tid; gi < ngran; gi += RN_THREADS)
+      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = z;
+    return;
+  }
+  int id = tok[t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  const u32x4* row = reinterpret_cast<const u32x4*>(embed + (size_t)id * d);
+  float vals[RN_MAXG][8];
+  f32x4 gg[RN_MAXG][2];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < RN_MAXG; ++it) {
+    const int gi = min(it * RN_THREADS + tid, ngran - 1);
+    const bool live = it * RN_THREADS + tid < ngran;
+    const u32x4 v = row[gi];
+    gg[it][0] = *reinterpret_cast<const f32x4*>(g + gi * 8);
+    gg[it][1] = *reinterpret_cast<const f32x4*>(g + gi * 8 + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vals[it][2 * e] = __builtin_bit_cast(float, v[e] << 16);
+      vals[it][2 * e + 1] = __builtin_bit_cast(float, v[e] & 0xffff0000u);
+    }
+    if (live) {
+      float* xr = x + (size_t)t * d + gi * 8;
+      *reinterpret_cast<f32x4*>(xr) = f32x4{vals[it][0], vals[it][1], vals[it][2], vals[it][3]};
+      *reinterpret_cast<f32x4*>(xr + 4) = f32x4{vals[it][4], vals[it][5], vals[it][6], vals[it][7]};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += vals[it][e] * vals[it][e];
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  __shared__ float part[RN_THREADS / WAVE];
+  if ((tid & 63) == 0) part[tid >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < RN_THREADS / WAVE; ++w) tot += part[w];
+  const float inv = 1.0f / sqrtf(tot / d + eps);
+#pragma unroll
+  for (int it = 0; it < RN_MAXG; ++it) {
+    int gi = it * RN_THREADS + tid;
+    if (gi < ngran) {
+      u32x4 pk;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        pk[e] = pack2bf(vals[it][2 * e] * gg[it][0][2 * e] * inv,
+                        vals[it][2 * e + 1] * gg[it][0][2 * e + 1] * inv);
+        pk[2 + e] = pack2bf(vals[it][4 + 2 * e] * gg[it][1][2 * e] * inv,
+                            vals[it][4 + 2 * e + 1] * gg[it][1][2 * e + 1] * inv);
+      }
+      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = pk;
+    }
+  }
+}
+
+int launch_embed_norm(const uint16_t* embed, const int32_t* tok, int T, int d, int vocab, float* x,
+                      const float* g, int tp, float eps, uint16_t* hp, hipStream_t st) {
+  if ((d & 7) || d > 8 * RN_THREADS * RN_MAXG) return TRJ_ERR_BAD_SHAPE;
+  embed_norm_kernel<<<tp, RN_THREADS, 0, st>>>(embed, tok, T, d, vocab, x, g, tp, eps, hp);
   return check_launch();
 }
 

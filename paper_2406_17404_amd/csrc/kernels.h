@@ -56,6 +56,29 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
 int launch_attn_items(const int32_t* node_off, const int32_t* prefix_len, const int32_t* kv_off,
                       const int32_t* status_dev, int B, int rows_per_item, int qg_max,
                       int blocks_per_item, int nsplit_max, int32_t* items, hipStream_t st);
+// A prepared tree template (device pointers into the caller's buffer): what depends on the
+// tree alone.  hdr: 8 words {magic, B, T, head_dim, max_pos}; tstatus[B]: 1 = malformed tree;
+// tnoff[B+1]: the row ranges it was made for; tseq[T]: row -> sequence (-1: none);
+// cs[max_pos][head_dim/2]: cos, sin of position * theta^(-2j/head_dim).
+struct TemplateView {
+  int32_t* hdr;
+  int32_t* depth;
+  uint64_t* anc;
+  int32_t* tstatus;
+  int32_t* tnoff;
+  int32_t* tseq;
+  float2* cs;
+};
+int launch_template_prepare(const int32_t* parent, const int32_t* node_off, int B, int T, int dh,
+                            int max_pos, float theta, const TemplateView& v, hipStream_t st);
+// Everything a step needs besides the template: slot checks (status_dev), slot / position /
+// sequence of every row, the bf16 attention work list (items may be null), zero fill.
+int launch_template_step_prep(const TemplateView& v, const int32_t* node_off, const int32_t* kv_off,
+                              const int32_t* prefix_len, int B, int T, int dh, int max_pos, int s_pool,
+                              int max_seq_slots, int32_t* status_dev, int32_t* row_slot,
+                              int32_t* row_pos, int32_t* row_seq, int rows_per_item, int qg_max,
+                              int blocks_per_item, int nsplit_max, int32_t* items, void* zero,
+                              size_t zero_bytes, hipStream_t st);
 int launch_argmax(const float* logits, int T, int V, int32_t* out, hipStream_t st);
 int launch_accept(const int32_t* argmax, const int32_t* tok, const int32_t* parent,
                   const int32_t* node_off, const int32_t* status_in, int B, int T,
@@ -80,7 +103,8 @@ int launch_rmsnorm_f32(const float* x, const float* g, int T, int d, float eps, 
                        hipStream_t st);
 int launch_gemm_f32(const float* x, const float* w, int T, int n_in, int n_out, int add_to,
                     float* y, hipStream_t st);
-int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* row_slot, int T,
+int launch_rope_kv_f32(const float* qkv, const float2* cs, const int32_t* cs_row,
+                       const int32_t* row_slot, int T,
                        int n_heads, int n_kv_heads, int dh, int s_pool, float* q, float* k_layer,
                        float* v_layer, hipStream_t st);
 int launch_silu_mul_f32(const float* gu, int T, int F, float* act, hipStream_t st);
@@ -99,8 +123,12 @@ int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, 
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
                         uint16_t* act, hipStream_t st);
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* row_slot,
-                    uint16_t* q, uint16_t* k_layer, uint16_t* v_layer, hipStream_t st);
+                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* cs_row,
+                    const int32_t* row_slot, uint16_t* q, uint16_t* k_layer, uint16_t* v_layer,
+                    hipStream_t st);
+// x[t] = E[tok[t]] (fp32) and h = RMSNorm(x) * g in the tiled bf16 activation layout, one launch
+int launch_embed_norm(const uint16_t* embed, const int32_t* tok, int T, int d, int vocab, float* x,
+                      const float* g, int tp, float eps, uint16_t* hp, hipStream_t st);
 int launch_reduce_norm(const float* partial, int n_split, float* x, const float* g, int T, int d,
                        int tp, float eps, uint16_t* hp, hipStream_t st);
 int launch_sum_splits(const float* partial, int n_split, size_t n, float* y, hipStream_t st);
@@ -126,7 +154,8 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
               int32_t B, int32_t T, int32_t max_seq_slots, void* workspace, size_t ws_bytes,
               float* logits, int32_t* argmax_out, int32_t* accept_len, int32_t* best_node,
               int32_t* path, int32_t* bonus_tok, int32_t* new_len, int32_t* status_dev,
-              bool with_head, hipStream_t st);
+              bool with_head, hipStream_t st, const TemplateView* tmpl = nullptr, int max_pos = 0);
+size_t template_carve(void* base, int B, int T, int dh, int max_pos, TemplateView* v);
 size_t step_workspace_bytes(const trj_model_desc& m, int B, int T, int max_seq_slots);
 int check_model(const trj_model_desc* m);
 

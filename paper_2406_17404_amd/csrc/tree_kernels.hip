@@ -97,12 +97,11 @@ __global__ void prep_clear_kernel(int32_t* depth, int32_t* anc_words, int32_t* r
 // over the chunk gives every sequence its place.  With one
 // chunk (B <= 1024) the sequences are first ranked by length, longest first (ties by
 // index), so that the long ones start early and the launch ends evenly.
-__global__ __launch_bounds__(1024) void attn_items_kernel(
+__device__ inline void attn_items_body(
     const int32_t* __restrict__ node_off, const int32_t* __restrict__ prefix_len,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ status, int B,
     int rows_per_item, int qg_max, int blocks_per_item, int nsplit_max,
-    int32_t* __restrict__ items) {
-  __shared__ int32_t key[1024], cnt[1024], scan[1024];
+    int32_t* __restrict__ items, int32_t* key, int32_t* cnt, int32_t* scan) {
   const int tid = threadIdx.x;
   int carry = 0;
   for (int base = 0; base < B; base += 1024) {
@@ -156,6 +155,16 @@ __global__ __launch_bounds__(1024) void attn_items_kernel(
   if (tid == 0) items[(size_t)B * qg_max * nsplit_max * 8] = carry;
 }
 
+__global__ __launch_bounds__(1024) void attn_items_kernel(
+    const int32_t* __restrict__ node_off, const int32_t* __restrict__ prefix_len,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ status, int B,
+    int rows_per_item, int qg_max, int blocks_per_item, int nsplit_max,
+    int32_t* __restrict__ items) {
+  __shared__ int32_t key[1024], cnt[1024], scan[1024];
+  attn_items_body(node_off, prefix_len, kv_off, status, B, rows_per_item, qg_max, blocks_per_item,
+                  nsplit_max, items, key, cnt, scan);
+}
+
 int launch_attn_items(const int32_t* node_off, const int32_t* prefix_len, const int32_t* kv_off,
                       const int32_t* status_dev, int B, int rows_per_item, int qg_max,
                       int blocks_per_item, int nsplit_max, int32_t* items, hipStream_t st) {
@@ -175,6 +184,111 @@ int launch_tree_prep(const int32_t* parent, const int32_t* node_off, const int32
       static_cast<uint32_t*>(zero), zw);
   tree_prep_kernel<<<B, TRJ_N_MAX, 0, st>>>(parent, node_off, kv_off, prefix_len, T, s_pool,
                                             max_seq_slots, depth, anc, status_dev, row_slot, row_pos, row_seq);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------ static tree template
+// The paper verifies with ONE fixed sparse tree in every step (appendix "Templates for
+// Token Tree"), so everything that depends on the tree alone is computed once into a
+// caller-owned buffer: validity, depth and ancestor bits of every row, the row -> sequence
+// map, and the rotary table over positions 0..max_pos-1.  A step then needs one small
+// kernel for what depends on the prefix lengths: slot range checks, slot and position of
+// every row, the attention launch's work list, and the zero fill of the step's padding.
+constexpr int32_t TMPL_MAGIC = 0x54724a54;
+
+__global__ void tmpl_finish_kernel(const int32_t* __restrict__ node_off, int B, int T, int dh,
+                                   int max_pos, const int32_t* __restrict__ tstatus,
+                                   int32_t* __restrict__ hdr, int32_t* __restrict__ tnoff,
+                                   int32_t* __restrict__ tseq) {
+  // one workgroup per sequence; tseq was cleared to -1 before
+  const int s = blockIdx.x, i = threadIdx.x;
+  if (s == 0 && i == 0) {
+    hdr[0] = TMPL_MAGIC; hdr[1] = B; hdr[2] = T; hdr[3] = dh; hdr[4] = max_pos;
+    hdr[5] = hdr[6] = hdr[7] = 0;
+    tnoff[B] = node_off[B];
+  }
+  if (i == 0) tnoff[s] = node_off[s];
+  if (tstatus[s] != 0) return;  // a malformed sequence owns no rows
+  const int r0 = node_off[s], n = node_off[s + 1] - r0;
+  if (i < n) tseq[r0 + i] = s;
+}
+
+int launch_template_prepare(const int32_t* parent, const int32_t* node_off, int B, int T, int dh,
+                            int max_pos, float theta, const TemplateView& v, hipStream_t st) {
+  int rc = launch_tree_prep(parent, node_off, nullptr, nullptr, B, T, 0, 0, v.depth, v.anc, v.tstatus,
+                            nullptr, nullptr, nullptr, nullptr, 0, st);
+  if (rc != TRJ_OK) return rc;
+  fill_i32_kernel<<<(T + 255) / 256, 256, 0, st>>>(v.tseq, -1, T);
+  tmpl_finish_kernel<<<B, TRJ_N_MAX, 0, st>>>(node_off, B, T, dh, max_pos, v.tstatus, v.hdr, v.tnoff,
+                                              v.tseq);
+  rc = check_launch();
+  if (rc != TRJ_OK) return rc;
+  return launch_rope_table(nullptr, max_pos, dh, theta, v.cs, st);
+}
+
+__global__ __launch_bounds__(1024) void tmpl_step_prep_kernel(
+    TemplateView v, const int32_t* __restrict__ node_off, const int32_t* __restrict__ kv_off,
+    const int32_t* __restrict__ prefix_len, int B, int T, int dh, int max_pos, int s_pool,
+    int max_seq_slots, int32_t* __restrict__ status_dev, int32_t* __restrict__ row_slot,
+    int32_t* __restrict__ row_pos, int32_t* __restrict__ row_seq, int rows_per_item, int qg_max,
+    int blocks_per_item, int nsplit_max, int32_t* __restrict__ items, uint32_t* __restrict__ zero,
+    size_t zero_words) {
+  const int tid = threadIdx.x;
+  if (blockIdx.x > 0) {  // the other workgroups clear the step's padding
+    for (size_t i = (size_t)(blockIdx.x - 1) * 1024 + tid; i < zero_words;
+         i += (size_t)(gridDim.x - 1) * 1024)
+      zero[i] = 0;
+    return;
+  }
+  __shared__ int32_t key[1024], cnt[1024], scan[1024];
+  __shared__ int32_t hdr_bad;
+  if (tid == 0)
+    hdr_bad = !(v.hdr[0] == TMPL_MAGIC && v.hdr[1] == B && v.hdr[2] == T && v.hdr[3] == dh &&
+                v.hdr[4] == max_pos);
+  __syncthreads();
+  for (int s = tid; s < B; s += 1024) {
+    // the step's row ranges must be the template's (which were validated when it was made)
+    bool ok = !hdr_bad && v.tstatus[s] == 0 && node_off[s] == v.tnoff[s] &&
+              node_off[s + 1] == v.tnoff[s + 1];
+    if (ok) {
+      const int n = v.tnoff[s + 1] - v.tnoff[s];
+      const int ko = kv_off[s], L = prefix_len[s];
+      if (ko < 0 || (ko & (TRJ_KV_BLOCK - 1)) || L < 0 || (long)ko + L + n > (long)s_pool ||
+          (long)L + n > (long)max_seq_slots || (long)L + n > (long)max_pos)
+        ok = false;
+    }
+    status_dev[s] = ok ? 0 : 1;
+  }
+  __threadfence_block();
+  __syncthreads();
+  for (int t = tid; t < T; t += 1024) {
+    const int s = hdr_bad ? -1 : v.tseq[t];
+    const bool bad = s < 0 || s >= B || status_dev[s] != 0;
+    const int L = bad ? 0 : prefix_len[s];
+    row_slot[t] = bad ? -1 : kv_off[s] + L + (t - v.tnoff[s]);
+    row_pos[t] = bad ? 0 : L + v.depth[t];
+    row_seq[t] = bad ? -1 : s;
+  }
+  if (items) {
+    __syncthreads();
+    attn_items_body(node_off, prefix_len, kv_off, status_dev, B, rows_per_item, qg_max,
+                    blocks_per_item, nsplit_max, items, key, cnt, scan);
+  }
+}
+
+int launch_template_step_prep(const TemplateView& v, const int32_t* node_off, const int32_t* kv_off,
+                              const int32_t* prefix_len, int B, int T, int dh, int max_pos, int s_pool,
+                              int max_seq_slots, int32_t* status_dev, int32_t* row_slot,
+                              int32_t* row_pos, int32_t* row_seq, int rows_per_item, int qg_max,
+                              int blocks_per_item, int nsplit_max, int32_t* items, void* zero,
+                              size_t zero_bytes, hipStream_t st) {
+  const size_t zw = zero ? zero_bytes / 4 : 0;
+  size_t zwgs = (zw + 16 * 1024 - 1) / (16 * 1024);  // 16 words per thread and pass
+  if (zwgs > 512) zwgs = 512;
+  tmpl_step_prep_kernel<<<(unsigned)(1 + zwgs), 1024, 0, st>>>(
+      v, node_off, kv_off, prefix_len, B, T, dh, max_pos, s_pool, max_seq_slots, status_dev, row_slot,
+      row_pos, row_seq, rows_per_item, qg_max, blocks_per_item, nsplit_max, items,
+      static_cast<uint32_t*>(zero), zw);
   return check_launch();
 }
 

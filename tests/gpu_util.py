@@ -90,10 +90,17 @@ def read_pool(kp, vp, layer, batch, s, n, dh):
     return layouts.pool_to_kv(kp[layer], vp[layer], dh, int(batch.kv_off_h[s]), n)
 
 
-def run_step(shape, desc, dw, batch, kp_h, vp_h, want_logits=True):
-    """tr_verify_step through the binding.  kp_h / vp_h: host pools [layers, H, s_pool*dh]
-    fp32 (bf16-representable for bf16 models).  Returns a dict of numpy results plus the
-    pools after the step."""
+def make_template(desc, batch, max_pos):
+    """A prepared tree template (device buffer) for the batch's trees."""
+    tmpl = torch.empty(b.tr_template_bytes(desc, batch.B, batch.T, max_pos), dtype=torch.uint8, device=DEV)
+    b.tr_template_prepare(desc, batch.parent, batch.node_off, batch.B, batch.T, max_pos, tmpl)
+    return tmpl
+
+
+def run_step(shape, desc, dw, batch, kp_h, vp_h, want_logits=True, tmpl=None, max_pos=0):
+    """tr_verify_step (or, with a prepared template, tr_verify_step_template) through the
+    binding.  kp_h / vp_h: host pools [layers, H, s_pool*dh] fp32 (bf16-representable for
+    bf16 models).  Returns a dict of numpy results plus the pools after the step."""
     dt = tdtype(shape.dtype)
     kp, vp = to_dev(kp_h, dt), to_dev(vp_h, dt)
     stride = kv_heads(shape) * batch.s_pool * shape.head_dim
@@ -104,10 +111,14 @@ def run_step(shape, desc, dw, batch, kp_h, vp_h, want_logits=True):
     out = {k: torch.full((n,), -7, dtype=torch.int32, device=DEV)
            for k, n in dict(argmax=T, accept_len=B, best=B, bonus=B, new_len=B, status=B).items()}
     path = torch.full((B, b.N_MAX), -7, dtype=torch.int32, device=DEV)
-    b.tr_verify_step(desc, dw.struct, kp, vp, stride, batch.s_pool, batch.tok, batch.parent,
-                     batch.node_off, batch.kv_off, batch.prefix, B, T, batch.max_seq_slots, ws,
-                     logits, out["argmax"], out["accept_len"], out["best"], path, out["bonus"],
-                     out["new_len"], out["status"])
+    head = (desc, dw.struct, kp, vp, stride, batch.s_pool, batch.tok, batch.parent, batch.node_off,
+            batch.kv_off, batch.prefix, B, T, batch.max_seq_slots)
+    tail = (ws, logits, out["argmax"], out["accept_len"], out["best"], path, out["bonus"],
+            out["new_len"], out["status"])
+    if tmpl is None:
+        b.tr_verify_step(*head, *tail)
+    else:
+        b.tr_verify_step_template(*head, tmpl, max_pos, *tail)
     torch.cuda.synchronize()
     res = {k: v.cpu().numpy() for k, v in out.items()}
     res["path"] = path.cpu().numpy()
