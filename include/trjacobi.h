@@ -215,8 +215,10 @@ int32_t kv_compact(void* k_pool, void* v_pool, size_t kv_layer_stride, const int
  * position prefix_len + depth, tree K/V written to the pool, tree attention, output
  * projection + residual, RMSNorm, SwiGLU FFN + residual}, final RMSNorm, LM head,
  * greedy argmax, longest accepted path, compaction.  logits ([T][vocab] fp32) may be
- * NULL when only the predictions are wanted (they are then kept in the workspace).  All other outputs
- * as in accept_path / kv_compact. */
+ * NULL when only the predictions are wanted: in bf16 mode the argmax is then taken in
+ * the LM head's epilogue and no logits are ever written to memory (same predictions,
+ * bit for bit, as with a logits buffer); in fp32 mode they are kept in the workspace.
+ * All other outputs as in accept_path / kv_compact. */
 int32_t tr_verify_step(const trj_model_desc* desc, const trj_weights* weights, void* k_pool,
                        void* v_pool, size_t kv_layer_stride, int32_t s_pool,
                        const int32_t* tok, const int32_t* parent, const int32_t* node_off,

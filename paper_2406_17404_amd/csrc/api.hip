@@ -73,6 +73,7 @@ struct StepWs {
   TreeWs t;
   float2* cs;
   float *x, *logits;
+  void* cand;  // bf16 mode without logits: argmax candidates of the LM head's epilogue
   // bf16 mode
   uint16_t *hp, *q, *op, *act;
   float* partial;
@@ -110,7 +111,11 @@ static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max
   carve_tree(c, m.dtype, B, T, m.n_heads, m.head_dim, max_seq_slots, &w->t);
   w->cs = c.take<float2>((size_t)T * (m.head_dim / 2));
   w->x = c.take<float>((size_t)T * d);
-  w->logits = need_logits ? c.take<float>((size_t)T * m.vocab) : nullptr;
+  // without a logits buffer from the caller the fp32 mode keeps them here; the bf16 mode
+  // takes the argmax in the LM head's epilogue and needs only its candidates
+  w->logits = need_logits && m.dtype != TRJ_BF16 ? c.take<float>((size_t)T * m.vocab) : nullptr;
+  w->cand = need_logits && m.dtype == TRJ_BF16
+                ? c.take<char>(gemm_lm_argmax_scratch_bytes(T, m.vocab)) : nullptr;
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     w->hp = c.take<uint16_t>((size_t)tp * d);
@@ -660,7 +665,12 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
       { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st)); }
     }
     if (!with_head) return TRJ_OK;
-    { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st)); }
+    if (!logits) {  // predictions only: argmax in the LM head's epilogue, no logits in memory
+      { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_lm_argmax(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, w.cand, argmax_out, st)); }
+    } else {
+      ProfScope ps_(KC_GEMM_LM, st);
+      TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st));
+    }
   } else {
     TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));
     for (int l = 0; l < m.n_layers; ++l) {
@@ -682,7 +692,7 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
     TRJ_TRY(launch_rmsnorm_f32(w.x, weights->g_final, T, d, m.rms_eps, w.h, st));
     TRJ_TRY(launch_gemm_f32(w.h, (const float*)weights->w_lm, T, d, V, 0, lg, st));
   }
-  { ProfScope ps_(KC_ARGMAX, st); TRJ_TRY(launch_argmax(lg, T, V, argmax_out, st)); }
+  if (lg) { ProfScope ps_(KC_ARGMAX, st); TRJ_TRY(launch_argmax(lg, T, V, argmax_out, st)); }
   { ProfScope ps_(KC_ACCEPT, st); TRJ_TRY(launch_accept(argmax_out, tok, parent, node_off, status_dev, B, T, accept_len, best_node,
                         path, bonus_tok, status_dev, st)); }
   ProfScope ps_(KC_KV_COMPACT, st);

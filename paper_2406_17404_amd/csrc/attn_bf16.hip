@@ -24,6 +24,7 @@
 
 #include "common.h"
 #include "kernels.h"
+#include "tree_vis.h"
 
 namespace trj {
 
@@ -103,12 +104,8 @@ __device__ inline void softmax_tile_tree(const f32x16& sacc, int key0, int hh, i
   float mx = NEG_BIG;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    bool vis = true;
     const int kk = key0 + 8 * (v >> 2) + 4 * hh + (v & 3);
-    if (kk >= L) {
-      const int j = kk - L;
-      vis = j < 64 ? ((anc0 >> j) & 1) : (j < 128 ? ((anc1 >> (j - 64)) & 1) : 0);
-    }
+    const bool vis = tree_key_visible(kk, L, anc0, anc1);
     sv[v] = vis ? sacc[v] * scale : NEG_BIG;
     mx = fmaxf(mx, sv[v]);
   }

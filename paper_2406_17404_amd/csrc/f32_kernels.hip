@@ -4,6 +4,7 @@
 // kernels at the top (embedding, rotary table) serve both modes.
 #include "common.h"
 #include "kernels.h"
+#include "tree_vis.h"
 
 namespace trj {
 
@@ -230,11 +231,7 @@ __global__ __launch_bounds__(64) void tree_attn_f32_kernel(
   const uint64_t a0 = anc[2 * (size_t)t], a1 = anc[2 * (size_t)t + 1];
   float mx = -INFINITY;
   for (int kk = lane; kk < nk; kk += 64) {
-    bool vis = kk < L;
-    if (!vis) {
-      int j = kk - L;
-      vis = j < 64 ? (a0 >> j) & 1 : (a1 >> (j - 64)) & 1;
-    }
+    const bool vis = tree_key_visible(kk, L, a0, a1);
     float sv = -INFINITY;
     if (vis) {
       float acc = 0.f;

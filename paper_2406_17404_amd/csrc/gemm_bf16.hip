@@ -57,6 +57,34 @@ struct EpiStoreF32 {
   }
 };
 
+// ---- epilogue: greedy argmax without logits (Eq. 1's arg max taken where the logits are
+// born).  Every wavefront reduces the 32 vocabulary rows of its tile for each of its 32
+// token columns and writes one candidate (value, index) per (token, row tile); a second,
+// small kernel picks the winner among a token's candidates.  Lowest index wins ties, NaN
+// never wins (a candidate that saw nothing keeps index INT32_MAX).
+struct ArgmaxCand {
+  float v;
+  int32_t i;
+};
+struct EpiArgmax {
+  ArgmaxCand* cand;  // [T][n_tiles]
+  int T, n_tiles;
+  __device__ void operator()(const f32x16& acc, int tile, int ttile, int lane, int) const {
+    float bv = -INFINITY;
+    int bi = INT32_MAX;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {  // ascending row index within the lane
+      const int row = tile * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (acc[v] > bv || (acc[v] == bv && row < bi)) { bv = acc[v]; bi = row; }
+    }
+    const float ov = __shfl_xor(bv, 32);
+    const int oi = __shfl_xor(bi, 32);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    const int t = ttile * 32 + (lane & 31);
+    if (lane < 32 && t < T) cand[(size_t)t * n_tiles + tile] = ArgmaxCand{bv, bi};
+  }
+};
+
 // ---- epilogue: act = silu(gate) * up, written bf16 in the tiled activation layout.
 // A TRJ_PACK_GATE_UP tile holds gate rows 16*tile.. in tile rows 0..15 and the matching
 // up rows in tile rows 16..31, i.e. register v pairs with register v + 8.
@@ -573,6 +601,42 @@ int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, 
                           int n_out, int split_k, float* y, hipStream_t st) {
   EpiStoreF32 e{y, n_out, T, (size_t)T * n_out};
   return launch_gemm(xp, w, tp, n_in, n_out, split_k, e, st);
+}
+
+// LM head with the argmax taken in the epilogue: argmax_out[t] = lowest index of the row
+// maximum of x W^T; cand: T * n_out / 32 candidates of scratch
+__global__ __launch_bounds__(256) void argmax_cand_kernel(const ArgmaxCand* __restrict__ cand,
+                                                          int n_tiles, int32_t* __restrict__ out) {
+  const ArgmaxCand* row = cand + (size_t)blockIdx.x * n_tiles;
+  float bv = -INFINITY;
+  int bi = INT32_MAX;
+  for (int j = threadIdx.x; j < n_tiles; j += 256) {
+    const ArgmaxCand c = row[j];
+    if (c.v > bv || (c.v == bv && c.i < bi)) { bv = c.v; bi = c.i; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(bv, o);
+    const int oi = __shfl_xor(bi, o);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+    out[blockIdx.x] = bi == INT32_MAX ? 0 : bi;
+  }
+}
+size_t gemm_lm_argmax_scratch_bytes(int T, int n_out) { return (size_t)T * (n_out / 32) * sizeof(ArgmaxCand); }
+int launch_gemm_lm_argmax(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_out,
+                          void* cand, int32_t* argmax_out, hipStream_t st) {
+  EpiArgmax e{static_cast<ArgmaxCand*>(cand), T, n_out / 32};
+  int rc = launch_gemm(xp, w, tp, n_in, n_out, 1, e, st);
+  if (rc != TRJ_OK) return rc;
+  argmax_cand_kernel<<<T, 256, 0, st>>>(static_cast<const ArgmaxCand*>(cand), n_out / 32, argmax_out);
+  return check_launch();
 }
 
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,

@@ -120,6 +120,9 @@ int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k);
 void gemm_bf16_describe_plan(int tp, int n_in, int n_out, int split_k, int32_t out[6]);
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
                           int n_out, int split_k, float* y, hipStream_t st);
+size_t gemm_lm_argmax_scratch_bytes(int T, int n_out);
+int launch_gemm_lm_argmax(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_out,
+                          void* cand, int32_t* argmax_out, hipStream_t st);
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
                         uint16_t* act, hipStream_t st);
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,

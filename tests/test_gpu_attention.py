@@ -115,6 +115,29 @@ def test_packed_ragged_batch_repeated_with_cold_caches():
             assert all(np.array_equal(a, c) for a, c in zip(first, got)), trial
 
 
+def test_full_width_two_query_groups_repeated_with_cold_caches():
+    """32 heads of 128, 128-node trees (two query groups of 64 rows that walk the same K/V
+    blocks), a tree of 66 nodes among them (its third query tile holds two rows whose own
+    bits sit in the second ancestor word): repeated with and without emptied caches, every
+    launch must give the same bits, and sampled heads must match the oracle."""
+    H, dh = 32, 128
+    cases = [case(200, H, dh, 1000, 128, "bf16"), case(201, H, dh, 333, 66, "bf16"),
+             case(202, H, dh, 64, 128, "bf16")]
+    heads = [0, 9, 31]
+    want = [O.tree_attention(c[0][:, heads], c[1][heads], c[2][heads], c[3], c[4]) for c in cases]
+    first = None
+    for trial in range(15):
+        if trial % 3 == 0:
+            torch.randn(64 * 1024 * 1024, device=DEV)
+        got = run_attention("bf16", H, dh, cases, align=32)
+        if first is None:
+            first = got
+            for g, w in zip(got, want):
+                assert rel_err(g[:, heads], w) <= TOL["bf16"]
+        else:
+            assert all(np.array_equal(a, c) for a, c in zip(first, got)), trial
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("H,n_kv,L,n", [(8, 2, 300, 64), (4, 1, 33, 100), (6, 3, 0, 17)])
 def test_grouped_query_heads_share_kv_planes(dtype, H, n_kv, L, n):

@@ -327,3 +327,45 @@ def test_step_can_be_captured_in_a_graph_and_replayed():
         step()                       # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(logits, ref["logits"])
+
+
+@pytest.mark.parametrize("n_rows,many", [(64, False), (128, False), (512, True)])
+def test_argmax_in_the_lm_head_epilogue_equals_argmax_of_the_logits(n_rows, many):
+    """Without a logits buffer the bf16 step takes the greedy argmax (Eq. 1) inside the LM
+    head's epilogue.  Its predictions must be the oracle's argmax of the logits that the
+    same step writes when it is given a buffer, ties included: the LM head here has two
+    identical rows in different tiles (their logits tie wherever they are the maximum,
+    the lower index must win) and zero rows everywhere else (ties at exactly 0)."""
+    import torch
+    from dataclasses import replace
+    shape = I.ModelShape(2, 512, 4, 128, 1408, 8192 if many else 2048, "bf16")
+    w = I.gen_weights(shape, 90)
+    v = w["w_lm"][7].copy()
+    w["w_lm"] = np.zeros_like(w["w_lm"])     # every other row ties at exactly 0
+    w["w_lm"][7] = w["w_lm"][8] = w["w_lm"][1234] = v   # ties inside one tile and across tiles
+    rng = np.random.default_rng(90)
+    per = 128 if many else n_rows
+    trees = [I.tree_random(per, rng) for _ in range(n_rows // per)]
+    toks = [I.gen_tokens(shape.vocab, per, 90, "tree", s) for s in range(len(trees))]
+    Ls = [int(v) for v in rng.integers(0, 200, size=len(trees))]
+    pkvs = [prefix_normal(shape, 90, s, L) if L else None for s, L in enumerate(Ls)]
+    if many:
+        plan = b.trj_dev_gemm_plan(n_rows, shape.d_model, shape.vocab, True)
+        print("LM head plan:", plan)
+        assert plan["many_rows"] == 1          # the packed-batch projection kernel takes the epilogue too
+    desc, dw = device_weights(shape, w)
+    batch = Batch(trees, Ls, toks)
+    H, dh = shape.kv_heads, shape.head_dim
+    kp, vp = nan_pool(2, H, batch.s_pool, dh, "bf16"), nan_pool(2, H, batch.s_pool, dh, "bf16")
+    for s in range(batch.B):
+        if Ls[s]:
+            for l in range(2):
+                fill_pool(kp, vp, l, batch, s, *pkvs[s][l])
+    with_logits = run_step(shape, desc, dw, batch, kp, vp, want_logits=True)
+    fused = run_step(shape, desc, dw, batch, kp, vp, want_logits=False)
+    am = O.greedy_argmax(with_logits["logits"])
+    assert np.array_equal(fused["argmax"], am)
+    assert set(am.tolist()) == {0, 7}        # every row is decided by a tie: the lowest index wins
+    for k in ("accept_len", "best", "bonus", "new_len", "status", "path"):
+        assert np.array_equal(fused[k], with_logits[k]), k
+    assert np.array_equal(fused["k_pool"], with_logits["k_pool"], equal_nan=True)
