@@ -83,6 +83,37 @@ def peaks_report(torch, b):
                              "the published peak"}
 
 
+def build_device_model(shape, seed, torch, b):
+    """Random-init N(0, 0.02) weights generated on the device (synthetic), packed into
+    the library's tiled layout one matrix at a time."""
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    desc = b.make_desc(shape)
+    dw = b.DeviceWeights(desc)
+    dt = torch.bfloat16
+    d, hd, F, V = shape.d_model, shape.n_heads * shape.head_dim, shape.d_ffn, shape.vocab
+    kvd = shape.kv_heads * shape.head_dim
+
+    def rnd(n_out, n_in):
+        return (torch.randn(n_out, n_in, device="cuda", dtype=torch.float32, generator=gen) * 0.02).to(dt)
+
+    ones = torch.ones(d, device="cuda", dtype=torch.float32)
+    for _ in range(shape.n_layers):
+        dw.add_layer(ones, rnd(hd + 2 * kvd, d), rnd(d, hd), ones, rnd(2 * F, d), rnd(d, F))
+    dw.set_globals(rnd(V, d), ones, rnd(V, d))
+    dw.finish()
+    torch.cuda.synchronize()
+    return desc, dw
+
+
+def gemm_bytes(T, n_in, n_out, e=2):
+    return n_out * n_in * e + T * (n_in + n_out) * e
+
+
+def attn_bytes(L, N, H, dh, e=2, Hkv=None):
+    """K and V of every K/V head once, q in and the output out."""
+    return 2 * (L + N) * (Hkv or H) * dh * e + 2 * N * H * dh * e
+
+
 def cpu_baseline(wl, n_sample_layers=None):
     """The CPU oracle on the same workload.  One layer is timed first; if the whole step then
     fits about 30 s of oracle work it is run whole (all layers, LM head, argmax, accept,

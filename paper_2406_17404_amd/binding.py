@@ -16,7 +16,8 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtrjacobi.so")
+# TRJ_LIB_PATH: another build of the same library (A/B measurements); default: the in-tree build
+LIB_PATH = os.environ.get("TRJ_LIB_PATH") or os.path.join(_HERE, "libtrjacobi.so")
 
 N_MAX = 128
 KV_BLOCK = 32

@@ -76,7 +76,7 @@ struct StepWs {
   void* cand;  // bf16 mode without logits: argmax candidates of the LM head's epilogue
   // bf16 mode
   uint16_t *hp, *q, *op, *act;
-  float* partial;
+  float *partial, *ssq;
   // fp32 mode
   float *h, *qkv, *qf, *of, *gu, *actf;
 };
@@ -124,6 +124,7 @@ static void carve_step(Carver& c, const trj_model_desc& m, int B, int T, int max
     w->act = c.take<uint16_t>((size_t)tp * F);
     int sk1 = gemm_bf16_split_k(d, tp, hd), sk2 = gemm_bf16_split_k(d, tp, F);
     w->partial = c.take<float>((size_t)(sk1 > sk2 ? sk1 : sk2) * T * d);
+    w->ssq = c.take<float>((size_t)RS_MAX_PARTS * tp);
   } else {
     w->h = c.take<float>((size_t)T * d);
     w->qkv = c.take<float>((size_t)T * (hd + 2 * kvd));
@@ -555,8 +556,9 @@ int32_t trj_linear(const void* x, const void* w_packed, int32_t T, int32_t n_in,
   float* part = c.take<float>((size_t)sk * T * n_out);
   if (c.off > ws_bytes) return TRJ_ERR_WORKSPACE_TOO_SMALL;
   TRJ_TRY(launch_tile_activation((const uint16_t*)x, T, n_in, tp, xp, st));
-  if (sk == 1) return launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, 1, y, st);
-  TRJ_TRY(launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, sk, part, st));
+  const RowScale none{nullptr, 0, tp, 0.f, 0.f};
+  if (sk == 1) return launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, 1, none, y, st);
+  TRJ_TRY(launch_gemm_store_f32(xp, (const uint16_t*)w_packed, T, tp, n_in, n_out, sk, none, part, st));
   return launch_sum_splits(part, sk, (size_t)T * n_out, y, st);
 }
 
@@ -645,31 +647,34 @@ int step_impl(const trj_model_desc* desc, const trj_weights* weights, void* k_po
   if (m.dtype == TRJ_BF16) {
     const int tp = padded_rows(T);
     const int sk_o = gemm_bf16_split_k(d, tp, hd), sk_d = gemm_bf16_split_k(d, tp, F);
+    // the norm's division is done by the projection that consumes hp (RowScale)
+    const RowScale rs{w.ssq, reduce_norm_parts(d), tp, 1.0f / (float)d, m.rms_eps};
+    const RowScale none{nullptr, 0, tp, 0.f, 0.f};
     { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_embed_norm((const uint16_t*)weights->embed, tok, T, d, V, w.x,
-                              weights->h_layers[0].g_attn, tp, m.rms_eps, w.hp, st)); }
+                              weights->h_layers[0].g_attn, tp, w.hp, w.ssq, st)); }
     for (int l = 0; l < m.n_layers; ++l) {
       const trj_layer_weights& lw = weights->h_layers[l];
       uint16_t* kl = (uint16_t*)k_pool + (size_t)l * kv_layer_stride;
       uint16_t* vl = (uint16_t*)v_pool + (size_t)l * kv_layer_stride;
-      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, cs,
+      { ProfScope ps_(KC_GEMM_QKV, st); TRJ_TRY(launch_gemm_qkv(w.hp, (const uint16_t*)lw.wqkv, T, tp, d, H, Hkv, dh, s_pool, rs, cs,
                               cs_row, w.t.row_slot, w.q, kl, vl, st)); }
       TRJ_TRY(launch_tree_attn_bf16(w.q, kl, vl, w.t.anc, node_off, kv_off, prefix_len, status_dev,
                                     w.t.items, B, T, H, Hkv, dh, s_pool, max_seq_slots, scale, w.t.attn, 1, tp,
                                     w.op, st));
-      { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, w.partial, st)); }
-      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, m.rms_eps, w.hp, st)); }
-      { ProfScope ps_(KC_GEMM_GATE_UP, st); TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, w.act, st)); }
-      { ProfScope ps_(KC_GEMM_DOWN, st); TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, w.partial, st)); }
+      { ProfScope ps_(KC_GEMM_O, st); TRJ_TRY(launch_gemm_store_f32(w.op, (const uint16_t*)lw.wo, T, tp, hd, d, sk_o, none, w.partial, st)); }
+      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_o, w.x, lw.g_ffn, T, d, tp, w.hp, w.ssq, st)); }
+      { ProfScope ps_(KC_GEMM_GATE_UP, st); TRJ_TRY(launch_gemm_gate_up(w.hp, (const uint16_t*)lw.w_gate_up, tp, d, F, rs, w.act, st)); }
+      { ProfScope ps_(KC_GEMM_DOWN, st); TRJ_TRY(launch_gemm_store_f32(w.act, (const uint16_t*)lw.w_down, T, tp, F, d, sk_d, none, w.partial, st)); }
       const float* g_next = l + 1 < m.n_layers ? weights->h_layers[l + 1].g_attn : weights->g_final;
       if (!with_head && l + 1 == m.n_layers) break;  // nothing reads the last FFN of a prompt pass
-      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, m.rms_eps, w.hp, st)); }
+      { ProfScope ps_(KC_REDUCE_NORM, st); TRJ_TRY(launch_reduce_norm(w.partial, sk_d, w.x, g_next, T, d, tp, w.hp, w.ssq, st)); }
     }
     if (!with_head) return TRJ_OK;
     if (!logits) {  // predictions only: argmax in the LM head's epilogue, no logits in memory
-      { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_lm_argmax(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, w.cand, argmax_out, st)); }
+      { ProfScope ps_(KC_GEMM_LM, st); TRJ_TRY(launch_gemm_lm_argmax(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, rs, w.cand, argmax_out, st)); }
     } else {
       ProfScope ps_(KC_GEMM_LM, st);
-      TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, lg, st));
+      TRJ_TRY(launch_gemm_store_f32(w.hp, (const uint16_t*)weights->w_lm, T, tp, d, V, 1, rs, lg, st));
     }
   } else {
     TRJ_TRY(launch_embed(weights->embed, tok, T, d, V, m.dtype, w.x, st));

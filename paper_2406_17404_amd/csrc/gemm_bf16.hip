@@ -37,11 +37,20 @@ struct GemmArgs {
   int chunks_per_split;  // phases per k-split
 };
 
+// RMSNorm with the division deferred to the consumer: the producer of the activations
+// writes bf16(x * g) (not yet divided by the row's norm) and, per row, partial sums of x^2
+// over PARTS column parts; a projection of those activations multiplies its accumulators by
+// 1 / sqrt(mean(x^2) + eps) of the token row before its epilogue.  (x*g*inv and (x*g)*inv
+// round to bf16 with the same relative error; the product with W is linear in inv.)  The
+// producer then needs no row-wide reduction and spreads over the whole chip.
 // acc layout of v_mfma_f32_32x32x16: lane l, register v -> tile row 8*(v/4) + 4*(l/32) +
 // v%4, tile column l%32.  Rows are output features, columns are token rows.
 
 // ---- epilogue: fp32 store, y[split][t][n_out]; 4 consecutive features per store
-struct EpiStoreF32 {
+template <bool SCALED>
+struct EpiStoreF32T {
+  static constexpr bool kScaled = SCALED;  // are the accumulators divided by the rows' norms first?
+  RowScale rs;
   float* y;
   int ld, T;
   size_t split_stride;
@@ -67,6 +76,8 @@ struct ArgmaxCand {
   int32_t i;
 };
 struct EpiArgmax {
+  static constexpr bool kScaled = true;
+  RowScale rs;
   ArgmaxCand* cand;  // [T][n_tiles]
   int T, n_tiles;
   __device__ void operator()(const f32x16& acc, int tile, int ttile, int lane, int) const {
@@ -89,6 +100,8 @@ struct EpiArgmax {
 // A TRJ_PACK_GATE_UP tile holds gate rows 16*tile.. in tile rows 0..15 and the matching
 // up rows in tile rows 16..31, i.e. register v pairs with register v + 8.
 struct EpiGateUp {
+  static constexpr bool kScaled = true;
+  RowScale rs;
   uint16_t* act;  // tiled, tp rows, d_ffn columns
   int tp;
   __device__ void operator()(const f32x16& acc, int tile, int ttile, int lane, int) const {
@@ -110,6 +123,8 @@ struct EpiGateUp {
 
 // ---- epilogue: rotary on q and k, q stored plain [T][H][dh], k and v into the pool.
 struct EpiQKV {
+  static constexpr bool kScaled = true;
+  RowScale rs;
   const float2* cs;         // [.][dh/2] cos, sin: row t of the table, or row cs_row[t] if given
   const int32_t* cs_row;    // optional: the table is indexed by position, this is each row's
   const int32_t* row_slot;  // pool slot of each row, -1 = skip
@@ -164,6 +179,38 @@ struct EpiQKV {
   }
 };
 
+// this lane's token row of each of MT token tiles: the partial sums of squares (all parts
+// asked for at once, clamped index; parts beyond the last are ignored when they are summed)
+template <int MT>
+__device__ inline void row_scale_load(const RowScale& rs, int ttile0, int lane, float (&ssq)[MT][RS_MAX_PARTS]) {
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int p = 0; p < RS_MAX_PARTS; ++p) ssq[m][p] = 0.f;
+  if (!rs.ssq) return;  // uniform
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int t = (ttile0 + m) * 32 + (lane & 31);
+#pragma unroll
+    for (int p = 0; p < RS_MAX_PARTS; ++p)  // no arithmetic on the loaded value here: it would wait for it
+      ssq[m][p] = rs.ssq[(size_t)min(p, rs.parts - 1) * rs.tp + t];
+  }
+}
+__device__ inline float row_scale_factor(const RowScale& rs, const float (&ssq)[RS_MAX_PARTS]) {
+  if (!rs.ssq) return 1.0f;
+  float s = 0.f;
+#pragma unroll
+  for (int p = 0; p < RS_MAX_PARTS; ++p) s += p < rs.parts ? ssq[p] : 0.f;  // fixed order
+  return 1.0f / sqrtf(s * rs.inv_d + rs.eps);
+}
+// a scaled copy for the epilogue (the accumulators themselves stay where they are)
+__device__ inline f32x16 scaled(const f32x16& acc, float f) {
+  f32x16 r;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) r[v] = acc[v] * f;
+  return r;
+}
+
 // Main loop.  Workgroup = RT row tiles x KW k-parts wavefronts, no loader.
 // The k-range is walked in phases of PH k-steps; the activations of a phase (PH*MT KiB)
 // sit in one of two LDS buffers.  Every wavefront
@@ -204,6 +251,10 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
   for (int m = 0; m < MT; ++m)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+  // the token rows' sums of squares are asked for now (oldest loads of the wavefront) and
+  // used only after the main loop
+  float ssq[Epi::kScaled ? MT : 1][RS_MAX_PARTS];
+  if constexpr (Epi::kScaled) row_scale_load<MT>(epi.rs, tb * MT, lane, ssq);
 
   if (ph0 < ph1) {
     const int n = (ph1 - ph0) * WS;  // k-steps of this wavefront
@@ -305,7 +356,12 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
   }
   if (kw == 0 && tile_ok) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m) epi(acc[m], tile, tb * MT + m, lane, blockIdx.y);
+    for (int m = 0; m < MT; ++m) {
+      if constexpr (Epi::kScaled)
+        epi(scaled(acc[m], row_scale_factor(epi.rs, ssq[m])), tile, tb * MT + m, lane, blockIdx.y);
+      else
+        epi(acc[m], tile, tb * MT + m, lane, blockIdx.y);
+    }
   }
 }
 
@@ -452,11 +508,23 @@ __global__ __launch_bounds__(RT * 64) void gemm_t_kernel(GemmArgs a, Epi epi) {
       x_load(ph + 2);
     }
   }
+  // the rows' norms are fetched only now: this kernel runs for a long time and has no
+  // registers to spare for them during the main loop
+  float rsf[MT];
+  if constexpr (Epi::kScaled) {
+    float ssq[MT][RS_MAX_PARTS];
+    row_scale_load<MT>(epi.rs, tb * MT, lane, ssq);
+#pragma unroll
+    for (int m = 0; m < MT; ++m) rsf[m] = row_scale_factor(epi.rs, ssq[m]);
+  }
 #pragma unroll
   for (int r = 0; r < WT; ++r)
     if (tile0 + r < ntiles) {
 #pragma unroll
-      for (int m = 0; m < MT; ++m) epi(acc[r][m], tile0 + r, tb * MT + m, lane, blockIdx.y);
+      for (int m = 0; m < MT; ++m) {
+        if constexpr (Epi::kScaled) epi(scaled(acc[r][m], rsf[m]), tile0 + r, tb * MT + m, lane, blockIdx.y);
+        else epi(acc[r][m], tile0 + r, tb * MT + m, lane, blockIdx.y);
+      }
     }
 }
 
@@ -598,8 +666,12 @@ int gemm_bf16_split_k(int n_out, int tp, int n_in) {
 }
 
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
-                          int n_out, int split_k, float* y, hipStream_t st) {
-  EpiStoreF32 e{y, n_out, T, (size_t)T * n_out};
+                          int n_out, int split_k, const RowScale& rs, float* y, hipStream_t st) {
+  if (rs.ssq) {
+    EpiStoreF32T<true> e{rs, y, n_out, T, (size_t)T * n_out};
+    return launch_gemm(xp, w, tp, n_in, n_out, split_k, e, st);
+  }
+  EpiStoreF32T<false> e{rs, y, n_out, T, (size_t)T * n_out};
   return launch_gemm(xp, w, tp, n_in, n_out, split_k, e, st);
 }
 
@@ -631,8 +703,8 @@ __global__ __launch_bounds__(256) void argmax_cand_kernel(const ArgmaxCand* __re
 }
 size_t gemm_lm_argmax_scratch_bytes(int T, int n_out) { return (size_t)T * (n_out / 32) * sizeof(ArgmaxCand); }
 int launch_gemm_lm_argmax(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_out,
-                          void* cand, int32_t* argmax_out, hipStream_t st) {
-  EpiArgmax e{static_cast<ArgmaxCand*>(cand), T, n_out / 32};
+                          const RowScale& rs, void* cand, int32_t* argmax_out, hipStream_t st) {
+  EpiArgmax e{rs, static_cast<ArgmaxCand*>(cand), T, n_out / 32};
   int rc = launch_gemm(xp, w, tp, n_in, n_out, 1, e, st);
   if (rc != TRJ_OK) return rc;
   argmax_cand_kernel<<<T, 256, 0, st>>>(static_cast<const ArgmaxCand*>(cand), n_out / 32, argmax_out);
@@ -640,48 +712,70 @@ int launch_gemm_lm_argmax(const uint16_t* xp, const uint16_t* w, int T, int tp, 
 }
 
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
-                        uint16_t* act, hipStream_t st) {
-  EpiGateUp e{act, tp};
+                        const RowScale& rs, uint16_t* act, hipStream_t st) {
+  EpiGateUp e{rs, act, tp};
   return launch_gemm(xp, w, tp, n_in, 2 * d_ffn, 1, e, st);
 }
 
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* cs_row,
-                    const int32_t* row_slot, uint16_t* q, uint16_t* k_layer, uint16_t* v_layer,
-                    hipStream_t st) {
-  EpiQKV e{cs, cs_row, row_slot, q, k_layer, v_layer, T, n_heads, n_kv_heads, dh, s_pool};
+                    int n_kv_heads, int dh, int s_pool, const RowScale& rs, const float2* cs,
+                    const int32_t* cs_row, const int32_t* row_slot, uint16_t* q, uint16_t* k_layer,
+                    uint16_t* v_layer, hipStream_t st) {
+  EpiQKV e{rs, cs, cs_row, row_slot, q, k_layer, v_layer, T, n_heads, n_kv_heads, dh, s_pool};
   return launch_gemm(xp, w, tp, n_in, (n_heads + 2 * n_kv_heads) * dh, 1, e, st);
 }
 
-// ------------------------------------------------------------------ split-k sum + residual + RMSNorm
-// One workgroup per token row: x[t] += sum_s partial[s][t] (fixed order), then
-// h = x * g / sqrt(mean(x^2) + eps) written bf16 in the tiled activation layout.  Rows
-// t >= T of the padded tile are written as zeros.  n_split == 0: norm only.
-constexpr int RN_THREADS = 512, RN_MAXG = 2, RN_SB = 8;
-__global__ __launch_bounds__(RN_THREADS) void reduce_norm_kernel(
+// ------------------------------------------------------------------ split-k sum + residual + norm input
+// x[t] += sum_s partial[s][t] (fixed order: s = 0, 1, ...), and the next projection's input
+// bf16(x * g) in the tiled activation layout, NOT yet divided by the row's norm: each
+// workgroup owns one column part (about 1024 columns) of one token row and writes that part's sum of x^2 to
+// ssq[part][t]; the consuming projection divides (RowScale).  Rows t >= T of the padded tile
+// are written as zeros.  Without partials the row comes from the embedding table instead
+// (x[t] = E[tok[t]], ids outside [0, vocab) clamped).
+constexpr int RN_MAX_THREADS = 256, RN_SB = 8;
+// column parts of a row: about 1024 columns each, at most RS_MAX_PARTS
+int reduce_norm_parts(int d) {
+  int p = (d + 1023) / 1024;
+  return p > RS_MAX_PARTS ? RS_MAX_PARTS : p;
+}
+// threads per workgroup (8 columns each): the part's share of the row, in whole wavefronts
+static int reduce_norm_threads(int d) {
+  const int ngran = d >> 3, parts = reduce_norm_parts(d);
+  return ((ngran + parts - 1) / parts + WAVE - 1) / WAVE * WAVE;
+}
+
+__global__ __launch_bounds__(RN_MAX_THREADS) void reduce_norm_kernel(
     const float* __restrict__ partial, int n_split, size_t split_stride, float* __restrict__ x,
-    const float* __restrict__ g, int T, int d, int tp, float eps, uint16_t* __restrict__ hp) {
-  const int t = blockIdx.x, tid = threadIdx.x;
+    const uint16_t* __restrict__ embed, const int32_t* __restrict__ tok, int vocab,
+    const float* __restrict__ g, int T, int d, int tp, uint16_t* __restrict__ hp,
+    float* __restrict__ ssq) {
+  const int t = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
   const int ngran = d >> 3;
+  const int gi_raw = part * blockDim.x + tid;
+  const bool live = gi_raw < ngran;
+  const int gi = min(gi_raw, ngran - 1);
   if (t >= T) {
     const u32x4 z = {0, 0, 0, 0};
-    for (int gi = tid; gi < ngran; gi += RN_THREADS)
-      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = z;
+    if (live) *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = z;
+    if (tid == 0) ssq[(size_t)part * tp + t] = 0.f;
     return;
   }
-  // the kernel is a latency chain (load, add, reduce, store): every load of a thread is
-  // issued before the first one is used, splits in batches of RN_SB with clamped indices
-  float vals[RN_MAXG][8];
-  f32x4 gg[RN_MAXG][2];
-  float ss = 0.f;
-#pragma unroll
-  for (int it = 0; it < RN_MAXG; ++it) {
-    const int gi = min(it * RN_THREADS + tid, ngran - 1);
-    const bool live = it * RN_THREADS + tid < ngran;
-    float* xr = x + (size_t)t * d + gi * 8;
-    f32x4 a = *reinterpret_cast<f32x4*>(xr), b = *reinterpret_cast<f32x4*>(xr + 4);
-    gg[it][0] = *reinterpret_cast<const f32x4*>(g + gi * 8);
-    gg[it][1] = *reinterpret_cast<const f32x4*>(g + gi * 8 + 4);
+  // every load of the thread is issued before the first one is used
+  float* xr = x + (size_t)t * d + gi * 8;
+  f32x4 a, b;
+  const f32x4 g0 = *reinterpret_cast<const f32x4*>(g + gi * 8);
+  const f32x4 g1 = *reinterpret_cast<const f32x4*>(g + gi * 8 + 4);
+  if (embed) {  // uniform over the launch
+    int id = tok[t];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(embed + (size_t)id * d + gi * 8);
+    a = f32x4{__builtin_bit_cast(float, v[0] << 16), __builtin_bit_cast(float, v[0] & 0xffff0000u),
+              __builtin_bit_cast(float, v[1] << 16), __builtin_bit_cast(float, v[1] & 0xffff0000u)};
+    b = f32x4{__builtin_bit_cast(float, v[2] << 16), __builtin_bit_cast(float, v[2] & 0xffff0000u),
+              __builtin_bit_cast(float, v[3] << 16), __builtin_bit_cast(float, v[3] & 0xffff0000u)};
+  } else {
+    a = *reinterpret_cast<f32x4*>(xr);
+    b = *reinterpret_cast<f32x4*>(xr + 4);
     for (int s0 = 0; s0 < n_split; s0 += RN_SB) {
       f32x4 pa[RN_SB], pb[RN_SB];
 #pragma unroll
@@ -698,121 +792,43 @@ __global__ __launch_bounds__(RN_THREADS) void reduce_norm_kernel(
         }
       }
     }
-    if (n_split > 0 && live) {
+  }
+  float ss = 0.f;
+  if (live) {
+    if (embed || n_split > 0) {
       *reinterpret_cast<f32x4*>(xr) = a;
       *reinterpret_cast<f32x4*>(xr + 4) = b;
     }
+    u32x4 pk = {pack2bf(a[0] * g0[0], a[1] * g0[1]), pack2bf(a[2] * g0[2], a[3] * g0[3]),
+                pack2bf(b[0] * g1[0], b[1] * g1[1]), pack2bf(b[2] * g1[2], b[3] * g1[3])};
+    *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = pk;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      vals[it][e] = a[e];
-      vals[it][4 + e] = b[e];
-      if (live) ss += a[e] * a[e] + b[e] * b[e];
-    }
+    for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
   }
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-  __shared__ float part[RN_THREADS / WAVE];
-  if ((tid & 63) == 0) part[tid >> 6] = ss;
+  __shared__ float wsum[RN_MAX_THREADS / WAVE];
+  if ((tid & 63) == 0) wsum[tid >> 6] = ss;
   __syncthreads();
-  float tot = 0.f;
-#pragma unroll
-  for (int w = 0; w < RN_THREADS / WAVE; ++w) tot += part[w];
-  const float inv = 1.0f / sqrtf(tot / d + eps);
-#pragma unroll
-  for (int it = 0; it < RN_MAXG; ++it) {
-    int gi = it * RN_THREADS + tid;
-    if (gi < ngran) {
-      u32x4 pk;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        pk[e] = pack2bf(vals[it][2 * e] * gg[it][0][2 * e] * inv,
-                        vals[it][2 * e + 1] * gg[it][0][2 * e + 1] * inv);
-        pk[2 + e] = pack2bf(vals[it][4 + 2 * e] * gg[it][1][2 * e] * inv,
-                            vals[it][4 + 2 * e + 1] * gg[it][1][2 * e + 1] * inv);
-      }
-      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = pk;
-    }
+  if (tid == 0) {
+    float tot = 0.f;
+    for (int w = 0; w < (int)blockDim.x / WAVE; ++w) tot += wsum[w];
+    ssq[(size_t)part * tp + t] = tot;
   }
 }
 
 int launch_reduce_norm(const float* partial, int n_split, float* x, const float* g, int T, int d,
-                       int tp, float eps, uint16_t* hp, hipStream_t st) {
-  if ((d & 7) || d > 8 * RN_THREADS * RN_MAXG) return TRJ_ERR_BAD_SHAPE;
-  reduce_norm_kernel<<<tp, RN_THREADS, 0, st>>>(partial, n_split, (size_t)T * d, x, g, T, d, tp,
-                                                eps, hp);
+                       int tp, uint16_t* hp, float* ssq, hipStream_t st) {
+  if ((d & 7) || reduce_norm_threads(d) > RN_MAX_THREADS) return TRJ_ERR_BAD_SHAPE;
+  reduce_norm_kernel<<<dim3(tp, reduce_norm_parts(d)), reduce_norm_threads(d), 0, st>>>(
+      partial, n_split, (size_t)T * d, x, nullptr, nullptr, 0, g, T, d, tp, hp, ssq);
   return check_launch();
 }
 
-// ------------------------------------------------------------------ embedding + first RMSNorm
-// One workgroup per token row: x[t] = E[tok[t]] as fp32 (ids outside [0, vocab) are clamped)
-// and h = x * g / sqrt(mean(x^2) + eps) in the tiled activation layout; padding rows of the
-// tile are written as zeros.
-__global__ __launch_bounds__(RN_THREADS) void embed_norm_kernel(
-    const uint16_t* __restrict__ embed, const int32_t* __restrict__ tok, int T, int d, int vocab,
-    float* __restrict__ x, const float* __restrict__ g, int tp, float eps,
-    uint16_t* __restrict__ hp) {
-  const int t = blockIdx.x, tid = threadIdx.x;
-  const int ngran = d >> 3;
-  if (t >= T) {
-    const u32x4 z = {0, 0, 0, 0};
-    for (int gi = tid; gi < ngran; gi += RN_THREADS)
-      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = z;
-    return;
-  }
-  int id = tok[t];
-  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-  const u32x4* row = reinterpret_cast<const u32x4*>(embed + (size_t)id * d);
-  float vals[RN_MAXG][8];
-  f32x4 gg[RN_MAXG][2];
-  float ss = 0.f;
-#pragma unroll
-  for (int it = 0; it < RN_MAXG; ++it) {
-    const int gi = min(it * RN_THREADS + tid, ngran - 1);
-    const bool live = it * RN_THREADS + tid < ngran;
-    const u32x4 v = row[gi];
-    gg[it][0] = *reinterpret_cast<const f32x4*>(g + gi * 8);
-    gg[it][1] = *reinterpret_cast<const f32x4*>(g + gi * 8 + 4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      vals[it][2 * e] = __builtin_bit_cast(float, v[e] << 16);
-      vals[it][2 * e + 1] = __builtin_bit_cast(float, v[e] & 0xffff0000u);
-    }
-    if (live) {
-      float* xr = x + (size_t)t * d + gi * 8;
-      *reinterpret_cast<f32x4*>(xr) = f32x4{vals[it][0], vals[it][1], vals[it][2], vals[it][3]};
-      *reinterpret_cast<f32x4*>(xr + 4) = f32x4{vals[it][4], vals[it][5], vals[it][6], vals[it][7]};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ss += vals[it][e] * vals[it][e];
-    }
-  }
-  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-  __shared__ float part[RN_THREADS / WAVE];
-  if ((tid & 63) == 0) part[tid >> 6] = ss;
-  __syncthreads();
-  float tot = 0.f;
-#pragma unroll
-  for (int w = 0; w < RN_THREADS / WAVE; ++w) tot += part[w];
-  const float inv = 1.0f / sqrtf(tot / d + eps);
-#pragma unroll
-  for (int it = 0; it < RN_MAXG; ++it) {
-    int gi = it * RN_THREADS + tid;
-    if (gi < ngran) {
-      u32x4 pk;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        pk[e] = pack2bf(vals[it][2 * e] * gg[it][0][2 * e] * inv,
-                        vals[it][2 * e + 1] * gg[it][0][2 * e + 1] * inv);
-        pk[2 + e] = pack2bf(vals[it][4 + 2 * e] * gg[it][1][2 * e] * inv,
-                            vals[it][4 + 2 * e + 1] * gg[it][1][2 * e + 1] * inv);
-      }
-      *reinterpret_cast<u32x4*>(hp + a_off(t, gi * 8, tp)) = pk;
-    }
-  }
-}
-
 int launch_embed_norm(const uint16_t* embed, const int32_t* tok, int T, int d, int vocab, float* x,
-                      const float* g, int tp, float eps, uint16_t* hp, hipStream_t st) {
-  if ((d & 7) || d > 8 * RN_THREADS * RN_MAXG) return TRJ_ERR_BAD_SHAPE;
-  embed_norm_kernel<<<tp, RN_THREADS, 0, st>>>(embed, tok, T, d, vocab, x, g, tp, eps, hp);
+                      const float* g, int tp, uint16_t* hp, float* ssq, hipStream_t st) {
+  if ((d & 7) || reduce_norm_threads(d) > RN_MAX_THREADS) return TRJ_ERR_BAD_SHAPE;
+  reduce_norm_kernel<<<dim3(tp, reduce_norm_parts(d)), reduce_norm_threads(d), 0, st>>>(
+      nullptr, 0, 0, x, embed, tok, vocab, g, T, d, tp, hp, ssq);
   return check_launch();
 }
 

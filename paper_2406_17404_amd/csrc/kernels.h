@@ -115,25 +115,39 @@ int launch_tree_attn_f32(const float* q, const float* k_layer, const float* v_la
                          int s_pool, int max_slots, float scale, float* out, hipStream_t st);
 
 // gemm_bf16.hip
+// RMSNorm with the division deferred to the consumer: the producer of the activations
+// writes bf16(x * g) (not yet divided by the row's norm) and, per row, partial sums of x^2
+// over `parts` column parts; a projection of those activations multiplies its accumulators
+// by 1 / sqrt(mean(x^2) + eps) of the token row before its epilogue.  (x*g*inv and (x*g)*inv
+// round to bf16 with the same relative error, and the product with W is linear in inv.)
+// The producer then needs no row-wide reduction and spreads over the whole chip.
+constexpr int RS_MAX_PARTS = 4;
+struct RowScale {
+  const float* ssq;  // [parts][tp]; nullptr: activations are used as they are
+  int parts, tp;
+  float inv_d, eps;
+};
+int reduce_norm_parts(int d);
 int gemm_bf16_split_k(int n_out, int tp, int n_in);
 int gemm_bf16_clamp_split(int n_out, int tp, int n_in, int split_k);
 void gemm_bf16_describe_plan(int tp, int n_in, int n_out, int split_k, int32_t out[6]);
 int launch_gemm_store_f32(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in,
-                          int n_out, int split_k, float* y, hipStream_t st);
+                          int n_out, int split_k, const RowScale& rs, float* y, hipStream_t st);
 size_t gemm_lm_argmax_scratch_bytes(int T, int n_out);
 int launch_gemm_lm_argmax(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_out,
-                          void* cand, int32_t* argmax_out, hipStream_t st);
+                          const RowScale& rs, void* cand, int32_t* argmax_out, hipStream_t st);
 int launch_gemm_gate_up(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int d_ffn,
-                        uint16_t* act, hipStream_t st);
+                        const RowScale& rs, uint16_t* act, hipStream_t st);
 int launch_gemm_qkv(const uint16_t* xp, const uint16_t* w, int T, int tp, int n_in, int n_heads,
-                    int n_kv_heads, int dh, int s_pool, const float2* cs, const int32_t* cs_row,
-                    const int32_t* row_slot, uint16_t* q, uint16_t* k_layer, uint16_t* v_layer,
-                    hipStream_t st);
-// x[t] = E[tok[t]] (fp32) and h = RMSNorm(x) * g in the tiled bf16 activation layout, one launch
+                    int n_kv_heads, int dh, int s_pool, const RowScale& rs, const float2* cs,
+                    const int32_t* cs_row, const int32_t* row_slot, uint16_t* q, uint16_t* k_layer,
+                    uint16_t* v_layer, hipStream_t st);
+// x[t] = E[tok[t]] (fp32), or x[t] += the split-k partial sums; hp = bf16(x * g) tiled and the
+// rows' partial sums of squares for the consumer's RowScale, one launch
 int launch_embed_norm(const uint16_t* embed, const int32_t* tok, int T, int d, int vocab, float* x,
-                      const float* g, int tp, float eps, uint16_t* hp, hipStream_t st);
+                      const float* g, int tp, uint16_t* hp, float* ssq, hipStream_t st);
 int launch_reduce_norm(const float* partial, int n_split, float* x, const float* g, int T, int d,
-                       int tp, float eps, uint16_t* hp, hipStream_t st);
+                       int tp, uint16_t* hp, float* ssq, hipStream_t st);
 int launch_sum_splits(const float* partial, int n_split, size_t n, float* y, hipStream_t st);
 int launch_tile_activation(const uint16_t* x, int T, int n, int tp, uint16_t* xp, hipStream_t st);
 
