@@ -37,7 +37,7 @@ int32_t trj_dev_gemm_plan(int32_t T, int32_t n_in, int32_t n_out, int32_t fused,
 
 /* Launch-shape knobs for experiments: "gemm_target_wgs" (workgroups a split-k projection
  * is split up to), "max_split_k", "gemm_cfg" (0: choose the workgroup shape per
- * projection, 1..5 force one), "gemm_big_t" (padded token rows from which the packed-batch
+ * projection, 1..6 force one), "gemm_big_t" (padded token rows from which the packed-batch
  * projection kernel is used, 0: never), "gemm_big_wt" (row tiles per wavefront of that
  * kernel: 2, 4, or 0 to choose per projection), "attn_target_wgs" (attention workgroups aimed at
  * per launch), "attn_min_bpw" (32-slot blocks per wavefront, at least), "attn_xchg_min_blocks" (blocks

@@ -185,7 +185,7 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
   const bool positive = value >= 1 && value <= (1 << 20);
   if (!strcmp(name, "gemm_target_wgs") && positive) g_tune.gemm_target_wgs = value;
   else if (!strcmp(name, "max_split_k") && positive) g_tune.max_split_k = value;
-  else if (!strcmp(name, "gemm_cfg") && value >= 0 && value <= 5) g_tune.gemm_cfg = value;
+  else if (!strcmp(name, "gemm_cfg") && value >= 0 && value <= 6) g_tune.gemm_cfg = value;
   else if (!strcmp(name, "gemm_big_t") && value >= 0) g_tune.gemm_big_t = value;
   else if (!strcmp(name, "gemm_big_wt") && (value == 0 || value == 2 || value == 4)) g_tune.gemm_big_wt = value;
   else if (!strcmp(name, "attn_target_wgs") && positive) g_tune.attn_target_wgs = value;

@@ -371,14 +371,14 @@ __global__ __launch_bounds__(RT * KW * 64) void gemm_p_kernel(GemmArgs a, Epi ep
 // 8 k-steps, 37.3 us with 16, 44.6 us with 4 and a ring of only 4; four k-parts: down
 // 23.5 -> 21.8 us with 16 k-steps, worse again with 8).  The weight ring stays 8 k-steps
 // deep and then spans two or four phases (16 deep: 36.6 us for gate/up).
-constexpr int p_phase(int mt, int kw) { return kw == 1 ? 8 : 16; }
+constexpr int p_phase(int mt, int kw, int rt = 4) { return rt == 3 ? 12 : (kw == 1 ? 8 : 16); }
 
 template <int MT, int RT, int KW, class Epi>
 static void launch_p(const uint16_t* xp, const uint16_t* w, int tp, int n_in, int n_out,
                      int split_k, const Epi& epi, hipStream_t st) {
-  constexpr int PH = p_phase(MT, KW);
+  constexpr int PH = p_phase(MT, KW, RT);
   constexpr int WS = PH / KW;
-  constexpr int PF = WS < 8 ? 8 : (WS < 16 ? WS : 16);
+  constexpr int PF = WS == 6 ? 6 : (WS < 8 ? 8 : (WS < 16 ? WS : 16));
   int ksteps = n_in >> 4, nph = (ksteps + PH - 1) / PH;
   if (split_k < 1) split_k = 1;
   if (split_k > nph) split_k = nph;
@@ -589,11 +589,19 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
           (long)((ntiles + rgt - 1) / rgt) * tblocks * splits(BIG_PH) >= 128;
   g.ph = g.big ? BIG_PH : (g.mt >= 3 ? 16 : 32);  // provisional: the shape decides it below
   g.split_k = splits(g.ph);
-  int shape = tune().gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8)
+  int shape = tune().gemm_cfg;  // 0 = choose; 1 = (4,1), 2 = (2,4), 3 = (2,2), 4 = (4,2), 5 = (1,8), 6 = (3,2)
   if (shape == 0) shape = (long)ntiles * g.split_k * tblocks >= 4 * 160 ? 1 : 3;
   // 128 token rows: twice the MFMA work per weight byte; two k-parts per row tile keep
   // more wavefronts on the stream (gate/up 58.7 -> 51.1 us)
   if (shape == 1 && g.mt >= 3 && tune().gemm_cfg == 0) shape = 4;
+  // What a launch of this kind is bound by is the rate at which ONE compute unit pulls its
+  // bytes (weights of its rows plus all activations of its k-range, about 46 GB/s each), so
+  // row tiles are spread over as many compute units as there are: when four tiles per
+  // workgroup leave a quarter of them idle and three do not overfill them, three tiles and
+  // two k-parts (gate/up at 64 rows: 172 -> 230 workgroups, 35.7 -> 34.1 us)
+  if (shape == 1 && tune().gemm_cfg == 0 && g.split_k == 1 && tblocks == 1 && (ntiles + 3) / 4 <= 192 &&
+      (ntiles + 2) / 3 <= 256)
+    shape = 6;
   // long k-range per workgroup: four k-parts (8 wavefronts) keep twice the loads in flight
   // per compute unit (128 rows: QKV 41.1 -> 35.2 us, down 33.2 -> 31.3 us); the output
   // projection's 64 k-steps per split are too short for it (128 rows: 17.3 against 18.0 us;
@@ -603,11 +611,11 @@ static GemmPlan plan_gemm(int tp, int n_in, int n_out, int split_k) {
   // workgroup and eight k-parts, so that the launch still has a workgroup on most compute
   // units (one compute unit pulls at most ~48 GB/s): 22.8 -> 20.2 us for 6144 x 4096
   if (shape == 2 && tune().gemm_cfg == 0 && (long)ntiles * g.split_k * tblocks <= 256) shape = 5;
-  g.rt = (shape == 1 || shape == 4) ? 4 : (shape == 5 ? 1 : 2);
+  g.rt = (shape == 1 || shape == 4) ? 4 : (shape == 5 ? 1 : (shape == 6 ? 3 : 2));
   g.kw = shape == 1 ? 1 : (shape == 2 ? 4 : (shape == 5 ? 8 : 2));
   if (g.big) { g.rt = 4; g.kw = 1; }
   else {
-    g.ph = p_phase(g.mt, g.kw);
+    g.ph = p_phase(g.mt, g.kw, g.rt);
     g.split_k = splits(g.ph);  // what launch_p computes from the same request
   }
   return g;
@@ -622,6 +630,7 @@ static int launch_gemm(const uint16_t* xp, const uint16_t* w, int tp, int n_in, 
 #define TRJ_P(M)                                                                             \
   do {                                                                                       \
     if (g.rt == 1) launch_p<M, 1, 8, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);           \
+    else if (g.rt == 3) launch_p<M, 3, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);      \
     else if (g.rt == 4 && g.kw == 2) launch_p<M, 4, 2, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st); \
     else if (g.rt == 4) launch_p<M, 4, 1, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);       \
     else if (g.kw == 4) launch_p<M, 2, 4, Epi>(xp, w, tp, n_in, n_out, g.split_k, epi, st);  \

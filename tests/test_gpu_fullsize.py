@@ -233,7 +233,7 @@ def test_full_width_layer_packed_1024_rows_many_rows_kernel():
                                      ("o", d, d, False), ("down", F, d, False)):
         plan = b.trj_dev_gemm_plan(1024, n_in, n_out, fused)
         say(f"plan at 1024 rows, {name}: {plan}")
-        assert plan["many_rows"] == 1 and plan["tiles_per_wave"] in (2, 4), name
+        assert plan["many_rows"] >= 1 and plan["tiles_per_wave"] in (2, 4), name
     rng = np.random.default_rng(1004)
     trees = [I.tree_random(64, rng) for _ in range(16)]
     Ls = [int(v) for v in rng.integers(64, 513, size=16)]

@@ -44,11 +44,11 @@ def test_bf16_linear(T, n_in, n_out, split_k):
     assert rel_err(got, want) <= 1e-5
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("T,n_in,n_out,split_k", [(64, 1040, 160, 1), (33, 4096, 6144, 1), (128, 2064, 96, 3),
                                                   (20, 528, 416, 2), (69, 1040, 224, 2)])
 def test_bf16_linear_every_workgroup_shape(cfg, T, n_in, n_out, split_k):
-    """Row tiles x k-parts per workgroup forced to each of the five shapes (row-tile counts
+    """Row tiles x k-parts per workgroup forced to each of the six shapes (row-tile counts
     that do not divide by the shape's rows, a k-range that ends inside a phase)."""
     try:
         b.trj_set_tunable("gemm_cfg", cfg)

@@ -352,7 +352,7 @@ def test_argmax_in_the_lm_head_epilogue_equals_argmax_of_the_logits(n_rows, many
     if many:
         plan = b.trj_dev_gemm_plan(n_rows, shape.d_model, shape.vocab, True)
         print("LM head plan:", plan)
-        assert plan["many_rows"] == 1          # the packed-batch projection kernel takes the epilogue too
+        assert plan["many_rows"] >= 1          # the packed-batch projection kernel takes the epilogue too
     desc, dw = device_weights(shape, w)
     batch = Batch(trees, Ls, toks)
     H, dh = shape.kv_heads, shape.head_dim
