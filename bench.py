@@ -74,9 +74,9 @@ def peaks_report(torch, b):
             "mfma_bf16_peak_source": "published dense rate = 256 CUs x 2.4 GHz x 4096 flop/clk/CU",
             "device_reports": info,
             "mfma_bf16_from_device_TFLOPs": round(cus * ghz * 4096 / 1e3, 1),
-            "hbm_from_device_GBps": round(bus / 8 * mem_ghz * 2, 1),
-            "hbm_from_device_note": "bus width / 8 x memory clock x 2 transfers per clock, from the figures "
-                                    "the device reports",
+            "hbm_from_device_GBps": round(bus / 8 * mem_ghz * 4, 1),
+            "hbm_from_device_note": "bus width / 8 x reported memory clock x 4 (HBM3E moves 8 Gbit/s per pin at the "
+                                    "2 GHz the device reports), from the figures the device reports",
             "read_kernel_GBps": read_gbps, "copy_kernel_GBps": copy_gbps,
             "measured_note": "streaming read of 1 GiB, and copy of 1 GiB (read + written bytes counted), by plain "
                              "kernels of the library in this run: what streaming reaches on this box beside "
