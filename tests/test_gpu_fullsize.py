@@ -71,7 +71,15 @@ def test_projection_shapes_sampled(name, n_in, n_out, T):
     wsmp = w[torch.from_numpy(ns).to(DEV)].double()
     want = (xs * wsmp).sum(1).cpu().numpy()       # fp64 dot products of the same values
     got = yh[ts, ns]
-    assert np.abs(got - want).max() <= 1e-5 * np.abs(yh).max()
+    tol = 1e-5 * np.abs(yh).max()
+    assert np.abs(got - want).max() <= tol
+    # the edge tiles in full: the last 32 token rows against every output feature, and every
+    # token row against the first and last 32 output features (fp64 products of the same values)
+    xd, wd = x.double(), w.double()
+    t0 = max(0, T - 32)
+    assert np.abs(yh[t0:] - (xd[t0:] @ wd.T).cpu().numpy()).max() <= tol
+    assert np.abs(yh[:, :32] - (xd @ wd[:32].T).cpu().numpy()).max() <= tol
+    assert np.abs(yh[:, -32:] - (xd @ wd[-32:].T).cpu().numpy()).max() <= tol
 
 
 @pytest.mark.parametrize("L", [512, 2048, 8192])
