@@ -13,12 +13,8 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
-def pytest_collection_modifyitems(config, items):
-    # GPU tests announce themselves (flushed) before they touch the device, so that a
-    # run that ends abruptly still names its case.
-    pass
-
-
+# GPU tests announce themselves (flushed) before they touch the device, so that a run that
+# ends abruptly still names its case.
 @pytest.fixture(autouse=True)
 def _announce(request):
     if request.node.get_closest_marker("gpu"):

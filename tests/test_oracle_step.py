@@ -255,3 +255,60 @@ def test_grouped_query_attention_reads_the_group_head():
     want = O.tree_attention(q, np.repeat(k, 3, axis=0), np.repeat(v, 3, axis=0), parent, 4)
     assert np.allclose(got, want, rtol=0, atol=1e-14)
     assert not np.allclose(got[:, 0], O.tree_attention(q, k[::-1].repeat(3, axis=0), v[::-1].repeat(3, axis=0), parent, 4)[:, 0])
+
+
+# ---- the storage hooks (a model of a 16-bit mode's storage; off by default)
+def test_storage_hooks_default_off_and_identity_changes_nothing():
+    w, prefix, pkv = setup(SMALL, 5, 9)
+    rng = np.random.default_rng(5)
+    tree = I.tree_random(11, rng)
+    tok = rng.integers(0, SMALL.vocab, size=11)
+    plain = O.decoder_tree_forward(SMALL, w, make_cache(SMALL, pkv, 9, 11), tok, tree, 9)
+    ident = {k: (lambda a: a) for k in ("h", "q", "kv", "p", "attn", "act")}
+    kv = make_cache(SMALL, pkv, 9, 11)
+    same = O.decoder_tree_forward(SMALL, w, kv, tok, tree, 9, storage=ident)
+    # the hooked attention divides after the product with V instead of before: rounding order only
+    assert np.abs(same - plain).max() <= 1e-12 * np.abs(plain).max()
+    assert O.decoder_tree_forward(SMALL, w, make_cache(SMALL, pkv, 9, 11), tok, tree, 9, storage={}) is not None
+    assert np.array_equal(O.decoder_tree_forward(SMALL, w, make_cache(SMALL, pkv, 9, 11), tok, tree, 9,
+                                                 storage=None), plain)
+
+
+def test_storage_hooks_see_the_tensors_they_name():
+    """Every hook is applied to the tensor its name says, once per layer and use: told apart
+    by shape (h twice per layer, K and V once each, the attention weights one vector per
+    node and head over prefix + root path)."""
+    shape = I.ModelShape(2, 32, 2, 16, 64, 50, "f32")
+    w, prefix, pkv = setup(shape, 6, 7)
+    tree = I.tree_chain(5)
+    tok = np.arange(5)
+    seen = {}
+
+    def rec(name):
+        def f(a):
+            seen.setdefault(name, []).append(np.asarray(a).shape)
+            return a
+        return f
+    O.decoder_tree_forward(shape, w, make_cache(shape, pkv, 7, 5), tok, tree, 7,
+                           storage={k: rec(k) for k in ("h", "q", "kv", "p", "attn", "act")})
+    n, H, dh, d, F, L = 5, 2, 16, 32, 64, 7
+    assert seen["h"] == [(n, d)] * 4
+    assert seen["q"] == [(n, H, dh)] * 2 and seen["kv"] == [(n, H, dh)] * 4
+    assert seen["attn"] == [(n, H, dh)] * 2 and seen["act"] == [(n, F)] * 2
+    # chain tree: node i sees the prefix and nodes 0..i
+    assert seen["p"] == [(L + i + 1,) for i in range(n) for _ in range(H)] * 2
+
+
+def test_storage_rounding_moves_the_result_by_about_the_rounding_step():
+    """Rounding the stored tensors to bf16 changes a shallow model's logits by a few units of
+    the bf16 step (2^-8 relative), not more and not nothing."""
+    w, prefix, pkv = setup(SMALL, 7, 9, std=0.15)
+    rng = np.random.default_rng(7)
+    tree = I.tree_random(12, rng)
+    tok = rng.integers(0, SMALL.vocab, size=12)
+    plain = O.decoder_tree_forward(SMALL, w, make_cache(SMALL, pkv, 9, 12), tok, tree, 9)
+    rnd = lambda a: I.bf16_round(np.asarray(a, np.float32)).astype(np.float64)
+    got = O.decoder_tree_forward(SMALL, w, make_cache(SMALL, pkv, 9, 12), tok, tree, 9,
+                                 storage={k: rnd for k in ("h", "q", "kv", "p", "attn", "act")})
+    dev = np.abs(got - plain).max() / np.abs(plain).max()
+    assert 1e-4 < dev < 3e-2
