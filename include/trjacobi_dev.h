@@ -40,7 +40,7 @@ int32_t trj_dev_gemm_plan(int32_t T, int32_t n_in, int32_t n_out, int32_t fused,
  * projection, 1..6 force one), "gemm_big_t" (padded token rows from which the packed-batch
  * projection kernel is used, 0: never), "gemm_big_wt" (row tiles per wavefront of that
  * kernel: 2, 4, or 0 to choose per projection), "attn_target_wgs" (attention workgroups aimed at
- * per launch), "attn_min_bpw" (32-slot blocks per wavefront, at least), "attn_xchg_min_blocks" (blocks
+ * per launch), "attn_min_bpw" (32-slot blocks per wavefront, at least; 0 = chosen from the tree size), "attn_xchg_min_blocks" (blocks
  * per workgroup from which the two wavefronts of a key stream split their K/V loads and
  * exchange halves through LDS).  Results do not
  * depend on them beyond fp32 summation order.  Unknown name: TRJ_ERR_BAD_SHAPE. */

@@ -189,7 +189,7 @@ int32_t trj_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_big_t") && value >= 0) g_tune.gemm_big_t = value;
   else if (!strcmp(name, "gemm_big_wt") && (value == 0 || value == 2 || value == 4)) g_tune.gemm_big_wt = value;
   else if (!strcmp(name, "attn_target_wgs") && positive) g_tune.attn_target_wgs = value;
-  else if (!strcmp(name, "attn_min_bpw") && positive) g_tune.attn_min_bpw = value;
+  else if (!strcmp(name, "attn_min_bpw") && (positive || value == 0)) g_tune.attn_min_bpw = value;
   else if (!strcmp(name, "attn_xchg_min_blocks") && positive) g_tune.attn_xchg_min_blocks = value;
   else return TRJ_ERR_BAD_SHAPE;
   return TRJ_OK;

@@ -481,7 +481,12 @@ void attn_bf16_plan(int B, int T, int n_heads, int max_seq_slots, int* ntw, int*
   const int items_est = B > (T + rows - 1) / rows ? B : (T + rows - 1) / rows;
   long cols = (long)items_est * n_heads;
   int b = (int)((nb * cols + tune().attn_target_wgs - 1) / tune().attn_target_wgs);
-  if (b < tune().attn_min_bpw * ks) b = tune().attn_min_bpw * ks;
+  // shortest walk worth a workgroup, in blocks per wavefront: one for trees of up to 64 nodes
+  // (measured at 64 nodes on 1024 slots: 13.7 against 14.1 us; at 16 on 8192: 30 against
+  // 32 us), two with two query groups, whose extra workgroups otherwise crowd the launch
+  // (128 nodes on 8192 slots: 47.5 against 49 us)
+  const int min_bpw = tune().attn_min_bpw > 0 ? tune().attn_min_bpw : (nmax > 64 ? 2 : 1);
+  if (b < min_bpw * ks) b = min_bpw * ks;
   if (b > nb) b = nb;
   *bpwg = b;
   *nsplit_max = (nb + b - 1) / b;

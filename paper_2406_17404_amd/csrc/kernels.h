@@ -13,7 +13,7 @@ struct Tunables {
   int attn_target_wgs = 256;   // attention workgroups per launch aimed at (one per CU)
   int gemm_big_wt = 0;         // row tiles per wavefront of the many-rows kernel (2, 4; 0 = choose)
   int attn_xchg_min_blocks = 48;  // blocks per workgroup from which wavefront pairs split their loads
-  int attn_min_bpw = 2;        // 32-slot blocks per wavefront, at least
+  int attn_min_bpw = 0;        // 32-slot blocks per wavefront, at least (0: 1 for trees of up to 64 nodes, else 2)
 };
 // trj_set_tunable writes the process-wide set; every entry point copies it once on entry
 // (TuneScope) and every launch plan of that call, on that thread, reads the copy, so the

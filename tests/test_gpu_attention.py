@@ -161,7 +161,7 @@ def test_bf16_launch_shapes_give_the_same_answer():
             assert rel_err(got, want) <= 1e-2
     finally:
         b.trj_set_tunable("attn_target_wgs", 256)
-        b.trj_set_tunable("attn_min_bpw", 2)
+        b.trj_set_tunable("attn_min_bpw", 0)
 
 
 def test_more_sequences_than_one_pass_of_the_work_list():
@@ -195,7 +195,7 @@ def test_packed_batch_with_splits_ties_and_both_query_groups():
         got = run_attention("bf16", H, dh, cases, align=32)
     finally:
         b.trj_set_tunable("attn_target_wgs", 256)
-        b.trj_set_tunable("attn_min_bpw", 2)
+        b.trj_set_tunable("attn_min_bpw", 0)
     for g, c in zip(got, cases):
         assert rel_err(g, O.tree_attention(*c)) <= 1e-2
 
@@ -222,7 +222,7 @@ def test_pair_exchange_single_sequence(pair_exchange, H, dh, L, n, wgs):
         got = run_attention("bf16", H, dh, [c])[0]
     finally:
         b.trj_set_tunable("attn_target_wgs", 256)
-        b.trj_set_tunable("attn_min_bpw", 2)
+        b.trj_set_tunable("attn_min_bpw", 0)
     assert np.isfinite(got).all()
     assert rel_err(got, O.tree_attention(*c)) <= 1e-2
 
