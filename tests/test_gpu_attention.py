@@ -89,6 +89,35 @@ def test_packed_ragged_batch(dtype):
         assert rel_err(g, O.tree_attention(*c)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_batches_sizes_at_block_and_tile_boundaries(seed):
+    """Random compositions biased towards the sizes where indexing changes: prefixes around
+    multiples of the 32-slot block, trees around 32, 64 and 128 rows, one to seven sequences,
+    1/2/4 query heads per K/V head, both head widths, random launch splits."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = ("f32", "bf16")[seed % 2]
+    dh = 64 if dtype == "f32" else int(rng.choice([64, 128]))
+    group = int(rng.choice([1, 2, 4]))
+    n_kv = int(rng.integers(1, 3))
+    H = n_kv * group
+    edge_L = [0, 1, 31, 32, 33, 63, 64, 65, 255, 256, 257]
+    edge_n = [1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128]
+    cases = []
+    for s in range(int(rng.integers(1, 8))):
+        L = int(rng.choice(edge_L)) if rng.random() < 0.6 else int(rng.integers(0, 900))
+        n = int(rng.choice(edge_n)) if rng.random() < 0.6 else int(rng.integers(1, 129))
+        cases.append(case(9100 + 16 * seed + s, H, dh, L, n, dtype, n_kv=n_kv if group > 1 else 0))
+    wgs = int(rng.choice([16, 256, 2048]))
+    try:
+        b.trj_set_tunable("attn_target_wgs", wgs)
+        got = run_attention(dtype, H, dh, cases, align=int(rng.choice([32, 64])))
+    finally:
+        b.trj_set_tunable("attn_target_wgs", 256)
+    for g, c in zip(got, cases):
+        assert np.isfinite(g).all(), (c[4], len(c[3]))
+        assert rel_err(g, O.tree_attention(*c)) <= TOL[dtype], (c[4], len(c[3]), wgs)
+
+
 def test_packed_ragged_batch_repeated_with_cold_caches():
     """The same ragged batch many times, every third launch after a 256 MiB write that
     empties the caches: launches that find their data in HBM run with a different timing

@@ -157,6 +157,38 @@ def test_packed_bf16_batch_with_ragged_prefixes():
     run_and_check(shape, w, trees, toks, Ls, pkvs, 1e-2)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_models_and_batches(seed):
+    """Random small models (width, FFN width and vocabulary any multiple of 32,
+    1/2/4 query heads per K/V head, 1-3 layers) on random packed batches whose sizes sit on
+    and around the tile and block boundaries; every output against the oracle."""
+    rng = np.random.default_rng(4200 + seed)
+    dtype = ("bf16", "f32")[seed % 2]
+    dh = 128 if dtype == "bf16" else 64
+    n_kv = int(rng.integers(1, 3))
+    H = n_kv * int(rng.choice([1, 2, 4]))
+    d = 32 * int(rng.integers(4, 13))
+    ffn = 32 * int(rng.integers(5, 30))
+    vocab = 32 * int(rng.integers(6, 47))
+    shape = I.ModelShape(int(rng.integers(1, 4)), d, H, dh, ffn, vocab, dtype, n_kv_heads=n_kv)
+    w = I.gen_weights(shape, 4300 + seed)
+    trees, toks, Ls, pkvs = [], [], [], []
+    rows = 0
+    for s in range(int(rng.integers(1, 6))):
+        n = int(rng.choice([1, 31, 32, 33, 64, 65, 128])) if rng.random() < 0.5 else int(rng.integers(1, 129))
+        L = int(rng.choice([0, 31, 32, 33, 64, 255])) if rng.random() < 0.5 else int(rng.integers(0, 300))
+        if rows + n > 320:
+            break
+        rows += n
+        trees.append(I.tree_random(n, rng) if rng.random() < 0.5 else I.tree_c1(n, rng) if n >= 8 else I.tree_chain(n))
+        toks.append(I.gen_tokens(shape.vocab, n, 4300 + seed, "tree", s))
+        Ls.append(L)
+        pkvs.append(prefix_normal(shape, 4300 + seed, s, L) if L else None)
+    res, summary = run_and_check(shape, w, trees, toks, Ls, pkvs, TOL[dtype])
+    print("random %s d=%d ffn=%d vocab=%d heads %d/%d layers %d, %d sequences, %d rows: worst logits rel err %.2e"
+          % (dtype, d, ffn, vocab, H, n_kv, shape.n_layers, len(trees), rows, max(e for e, _, _ in summary)))
+
+
 def test_packed_16_sequences_of_64_nodes():
     """The packed workload's structure (16 sequences, 64-node random trees, ragged prefixes
     U[256, 4096], 1024 tree rows in one launch) on a shrunken 2-layer model."""
