@@ -753,6 +753,29 @@ static int reduce_norm_threads(int d) {
   return ((ngran + parts - 1) / parts + WAVE - 1) / WAVE * WAVE;
 }
 
+// a, b += partial sums of splits 0 .. n_split-1 in that order, SB loads in flight at a time
+// (indices past the last split are clamped for the load and left out of the sum)
+template <int SB>
+__device__ __forceinline__ void add_splits(const float* __restrict__ pr, int n_split,
+                                           size_t split_stride, f32x4& a, f32x4& b) {
+  for (int s0 = 0; s0 < n_split; s0 += SB) {
+    f32x4 pa[SB], pb[SB];
+#pragma unroll
+    for (int j = 0; j < SB; ++j) {
+      const float* q = pr + min(s0 + j, n_split - 1) * split_stride;
+      pa[j] = *reinterpret_cast<const f32x4*>(q);
+      pb[j] = *reinterpret_cast<const f32x4*>(q + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < SB; ++j) {
+      if (s0 + j < n_split) {
+        a += pa[j];
+        b += pb[j];
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(RN_MAX_THREADS) void reduce_norm_kernel(
     const float* __restrict__ partial, int n_split, size_t split_stride, float* __restrict__ x,
     const uint16_t* __restrict__ embed, const int32_t* __restrict__ tok, int vocab,
@@ -785,22 +808,12 @@ __global__ __launch_bounds__(RN_MAX_THREADS) void reduce_norm_kernel(
   } else {
     a = *reinterpret_cast<f32x4*>(xr);
     b = *reinterpret_cast<f32x4*>(xr + 4);
-    for (int s0 = 0; s0 < n_split; s0 += RN_SB) {
-      f32x4 pa[RN_SB], pb[RN_SB];
-#pragma unroll
-      for (int j = 0; j < RN_SB; ++j) {
-        const float* pr = partial + min(s0 + j, n_split - 1) * split_stride + (size_t)t * d + gi * 8;
-        pa[j] = *reinterpret_cast<const f32x4*>(pr);
-        pb[j] = *reinterpret_cast<const f32x4*>(pr + 4);
-      }
-#pragma unroll
-      for (int j = 0; j < RN_SB; ++j) {
-        if (s0 + j < n_split) {  // same order for every launch: s = 0, 1, ...
-          a += pa[j];
-          b += pb[j];
-        }
-      }
-    }
+    // as many loads in flight as there are splits, up to RN_SB (n_split is uniform over
+    // the launch); the sum runs in the same order s = 0, 1, ... whichever batch is taken
+    const float* pr = partial + (size_t)t * d + gi * 8;
+    if (n_split <= 2) add_splits<2>(pr, n_split, split_stride, a, b);
+    else if (n_split <= 4) add_splits<4>(pr, n_split, split_stride, a, b);
+    else add_splits<RN_SB>(pr, n_split, split_stride, a, b);
   }
   float ss = 0.f;
   if (live) {
